@@ -1,0 +1,190 @@
+/*
+ * milora.h - C ABI of the MI355X routed-LoRA linear layers (MiLoRA inference hot path).
+ *
+ * The library implements, as HIP kernels for gfx950, the part of MiLoRA that runs for every
+ * request: the prompt-aware router evaluated once per Transformer layer at prefill
+ * (Sec. 3.3, Eq. 2 and Eq. 3) and the seven LoRA-carrying linears of a LLaMA-2 layer
+ * (Sec. 3.1, Eq. 1), where the low-rank term is added only for the requests whose cached
+ * route selected that linear, with the LoRA matrices gathered from the request's tenant.
+ *
+ * General rules
+ *  - Every pointer marked "device" is memory of the current HIP device, owned by the caller and
+ *    never freed, resized or retained by the library beyond the work it enqueues.  Pointers
+ *    marked "host" are ordinary host memory read during the call only.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *    and the call returns without synchronising.  Buffers must stay valid until that work is done.
+ *  - The library allocates nothing.  Calls that need scratch memory take a device `workspace`
+ *    of at least the size the matching *_workspace_bytes() function returns; its contents are
+ *    undefined afterwards.  Two calls that share a workspace must be ordered on one stream.
+ *  - Return value: MILORA_OK (0) or a negative milora_status.  Arguments are validated on the
+ *    host before anything is enqueued; values that live in device arrays (tenant ids, routes,
+ *    prompt spans) are checked by the kernels, which then skip the offending request as
+ *    documented per call and never read or write out of bounds because of it.
+ *  - Matrix conventions follow the paper: row vectors, x' = x W + x W^A W^B + b with
+ *    W in R^{d1 x d2}, W^A in R^{d1 x r}, W^B in R^{r x d2} (Eq. 1).
+ *  - Sites (the paper's N_mod = 7 modules, Sec. 3.1): 0 q, 1 k, 2 v, 3 o, 4 gate, 5 up, 6 down.
+ *    For a layer with hidden size d and FFN width F, (d1, d2) is (d, d) for q, k, v, o,
+ *    (d, F) for gate and up, (F, d) for down.
+ */
+#ifndef MILORA_H
+#define MILORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MILORA_NUM_SITES 7
+#define MILORA_MAX_RANK 256       /* largest LoRA rank accepted (the paper sweeps r up to 256, Sec. 4.5) */
+#define MILORA_MAX_DECODE_BATCH 128 /* largest B accepted by milora_layer_decode */
+#define MILORA_ROUTE_NONE 255     /* route value written for a request the router had to skip */
+
+typedef enum {
+  MILORA_OK = 0,
+  MILORA_EINVAL = -1,       /* null pointer, non-positive size, unknown enum value */
+  MILORA_ERANGE = -2,       /* a size beyond a documented limit */
+  MILORA_EUNSUPPORTED = -3, /* a combination the kernels do not cover (stated per call) */
+  MILORA_EHIP = -4,         /* a HIP call failed; see milora_last_hip_error() */
+  MILORA_EWORKSPACE = -5    /* workspace missing or smaller than *_workspace_bytes() */
+} milora_status;
+
+typedef enum { MILORA_BF16 = 0, MILORA_F32 = 1 } milora_dtype;
+typedef enum { MILORA_POOL_MEAN = 0, MILORA_POOL_LAST = 1 } milora_pool;
+typedef enum { MILORA_ACT_IDENTITY = 0, MILORA_ACT_TANH = 1, MILORA_ACT_RELU = 2, MILORA_ACT_GELU = 3 } milora_act;
+
+/* Storage of a base weight W (math shape d1 x d2).
+ *  MILORA_W_ROWMAJOR : [d2][d1], d1 contiguous (the usual linear-layer storage).
+ *  MILORA_W_PACKED   : the order milora_pack_weight() produces (bf16 only, d1 % 32 == 0 and
+ *                      d2 % 16 == 0): blocks of 16 output columns x 32 inputs, each block 1 KiB laid
+ *                      out lane-by-lane as the 16x16x32 matrix-core operand, blocks of one column
+ *                      group consecutive along d1.  Element (j, i) of the row-major array sits at
+ *                      ((j/16 * (d1/32) + i/32) * 64 + (i%32)/8 * 16 + j%16) * 8 + i%8.  */
+typedef enum { MILORA_W_ROWMAJOR = 0, MILORA_W_PACKED = 1 } milora_wlayout;
+
+/* Flags of milora_layer_decode. */
+#define MILORA_LAYER_RMSNORM 1u /* weightless RMS normalisation (eps 1e-5) in front of q/k/v and gate/up */
+
+/* Per-tenant LoRA stacks of ONE layer (host struct; the arrays it points to are device memory).
+ * Tenant t owns, for each site m, W^A stored [d1][r_t] row-major and W^B stored [r_t][d2]
+ * row-major, exactly as Eq. 1 writes them, in the same dtype as the base weights.  The rank r_t is
+ * per tenant and the same at all seven sites.  Matrices may live anywhere; the kernels use 16-byte
+ * loads when a matrix is 16-byte aligned and r_t is a multiple of 8 (bf16) or 4 (fp32), scalar
+ * loads otherwise. */
+typedef struct {
+  int32_t n_tenants;      /* T */
+  int32_t r_max;          /* an upper bound of rank[t] over all tenants, 1..MILORA_MAX_RANK */
+  const int32_t *rank;    /* device [T]: r_t; a tenant with r_t outside 1..r_max gets no LoRA term */
+  const void *const *A;   /* device [T*7] of device pointers, entry t*7+m -> W^A of (tenant t, site m) */
+  const void *const *B;   /* device [T*7] of device pointers, entry t*7+m -> W^B of (tenant t, site m) */
+} milora_adapters;
+
+/* The seven base weights of one layer (host struct of device pointers), all in `layout`. */
+typedef struct {
+  const void *W[MILORA_NUM_SITES]; /* W[m]: math shape d1 x d2 of site m */
+  int32_t layout;                  /* milora_wlayout */
+} milora_layer_weights;
+
+const char *milora_version(void);
+const char *milora_status_string(int status);
+/* The hipError_t (as int) of the most recent failed HIP call made by this thread, 0 if none. */
+int milora_last_hip_error(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * milora_route - the prompt-aware LoRA router of one layer (Sec. 3.3):
+ *   h_b = Pooler(H^l restricted to request b's prompt tokens)        (Eq. 2; last-token / average)
+ *   route[b] = argmax_j ( g(h_b) W_r^{l, tenant(b)} )_j               (Eq. 3 with top-1)
+ * Softmax is increasing, so the top-1 expert is taken on the logits; equal logits resolve to the
+ * lowest index.  Pooled state, activation and logits are kept in fp32 whatever `dtype` is.
+ * Runs once per layer per prompt; decode never calls it (the decisions are reused, Sec. 3.3).
+ *
+ *   H          device [M_tok][d], `dtype`: hidden states entering the layer, prompts in any packing
+ *   seq_start  device [B] int32: first row of request b's prompt in H
+ *   seq_len    device [B] int32: number of prompt tokens (valid rows) of request b, >= 1
+ *   tenant_id  device [B] int32 in [0, T)
+ *   Wr         device [T][7][d], `dtype`: column j of tenant t's d x 7 router matrix is the
+ *              contiguous d-vector Wr[t][j]; no bias
+ *   route_out  device [B] uint8: selected site per request (row `l` of the caller's route table)
+ *   logits_out device [B][7] float or NULL: the seven logits
+ *   workspace  device, milora_route_workspace_bytes(B, d, M_tok) bytes
+ * A request whose span leaves [0, M_tok), whose length is < 1 or whose tenant id is out of range
+ * gets route MILORA_ROUTE_NONE and NaN logits; the others are unaffected.
+ * Errors: EINVAL (null pointers, B/d/T/M_tok < 1, bad enums), EWORKSPACE, EHIP.
+ */
+size_t milora_route_workspace_bytes(int B, int d, int64_t M_tok);
+int milora_route(const void *H, int64_t M_tok, int d, int dtype, const int32_t *seq_start,
+                 const int32_t *seq_len, const int32_t *tenant_id, int B, int n_tenants,
+                 const void *Wr, int pool, int act, uint8_t *route_out, float *logits_out,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * milora_routed_linear - one LoRA-carrying linear for M rows (Eq. 1 with the layer-level gate of
+ * Sec. 3.3: a request's LoRA term is present only at the site its route selected):
+ *   b = row_to_req ? row_to_req[m] : m,  t = tenant_id[b]
+ *   Y[m] = X[m] W + bias + [route[b] == site] (X[m] W^A_{t,site}) W^B_{t,site}
+ * Accumulation is fp32; the low-rank intermediate stays fp32 and is added to the fp32 base result
+ * before the single rounding to `dtype`.
+ *
+ *   X           device [M][d1], `dtype`
+ *   row_to_req  device [M] int32 or NULL.  NULL means row m belongs to request m and needs M == B
+ *               (decode).  Prefill tokens and beams map several rows to one request.
+ *   W           device, math shape d1 x d2 in `w_layout` (MILORA_W_PACKED: bf16 only)
+ *   bias        device [d2] `dtype` or NULL
+ *   adapters    host struct, see milora_adapters
+ *   tenant_id   device [B] int32; route: device [B] uint8 (this layer's row of the route table)
+ *   Y           device [M][d2], `dtype`
+ *   workspace   device, milora_routed_linear_workspace_bytes(M, d1, d2, r_max) bytes
+ * A row whose request index, tenant id or tenant rank is out of range gets the base term only.
+ * Errors: EINVAL, ERANGE (r_max > MILORA_MAX_RANK), EUNSUPPORTED (packed layout with fp32 or with
+ * d1 % 32 != 0 or d2 % 16 != 0), EWORKSPACE, EHIP.
+ */
+size_t milora_routed_linear_workspace_bytes(int64_t M, int d1, int d2, int r_max);
+int milora_routed_linear(const void *X, int64_t M, int d1, int d2, int dtype,
+                         const int32_t *row_to_req, const void *W, int w_layout, const void *bias,
+                         const milora_adapters *adapters, int site, const int32_t *tenant_id,
+                         const uint8_t *route, int B, void *Y, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * milora_layer_decode - one decode step of B requests through the seven routed linears of a layer,
+ * using the cached routes (Sec. 3.3: the routing decisions of the prompt are reused for every
+ * generated token; nothing here reads prompts or router weights, and `route` is read-only).
+ * The paper fixes the seven linears (Sec. 3.1, Fig. 1); the glue between them is the smallest that
+ * chains them at their true shapes:
+ *   q, k, v = L_q(n(x)), L_k(n(x)), L_v(n(x))
+ *   a       = attn_out if given, else v   (what causal attention returns for a context of one token)
+ *   h       = x + L_o(a)
+ *   m       = silu(L_gate(n(h))) * L_up(n(h))
+ *   y       = h + L_down(m)
+ * where L_m is milora_routed_linear at site m without bias and n() is the identity, or
+ * u / sqrt(mean(u^2) + 1e-5) when MILORA_LAYER_RMSNORM is set.  Intermediates that feed a matrix
+ * product are rounded to `dtype`; the residual stream h is carried in fp32.
+ *
+ *   x         device [B][d] `dtype`;  y: device [B][d] `dtype` (may alias x)
+ *   weights   host struct of the seven base weights
+ *   attn_out  device [B][d] `dtype` or NULL
+ *   qkv_out   device [B][3d] `dtype` or NULL: q | k | v of every request, for the caller's attention
+ *   workspace device, milora_layer_decode_workspace_bytes(B, d, F, r_max) bytes
+ * Errors: EINVAL, ERANGE (B > MILORA_MAX_DECODE_BATCH, r_max > MILORA_MAX_RANK), EUNSUPPORTED
+ * (packed layout with fp32 or unaligned d, F), EWORKSPACE, EHIP.
+ */
+size_t milora_layer_decode_workspace_bytes(int B, int d, int F, int r_max);
+int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
+                        const milora_layer_weights *weights, const milora_adapters *adapters,
+                        const int32_t *tenant_id, const uint8_t *route, uint32_t flags,
+                        const void *attn_out, void *y, void *qkv_out, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * milora_pack_weight - one-time re-ordering of a bf16 base weight from MILORA_W_ROWMAJOR to
+ * MILORA_W_PACKED (see milora_wlayout), so that the decode kernels stream it with fully
+ * coalesced 1 KiB loads already in matrix-core operand order.  src and dst: device, d1*d2
+ * elements each, must not overlap.  Errors: EINVAL, EUNSUPPORTED (d1 % 32 or d2 % 16 nonzero), EHIP.
+ */
+int milora_pack_weight(const void *src_rowmajor, void *dst_packed, int d1, int d2, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MILORA_H */

@@ -1,0 +1,93 @@
+"""The C-ABI library loads without a GPU, exports every function the header declares, and its
+host-side logic (status strings, workspace sizing, argument validation) behaves as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_18035_amd import binding as mb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "milora.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(milora_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_name_the_same_entry_points():
+    assert declared_functions() == sorted(mb.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    L = mb.lib()
+    for name in declared_functions():
+        assert hasattr(L, name), f"{name} is declared in include/milora.h but not exported"
+
+
+def test_status_strings_and_version():
+    assert "gfx950" in mb.version()
+    for code in (0, -1, -2, -3, -4, -5):
+        assert mb.status_string(code) != "unknown status"
+    assert mb.status_string(-99) == "unknown status"
+    assert mb.last_hip_error() == 0
+
+
+def test_workspace_sizes_are_monotone_and_reject_bad_sizes():
+    assert mb.route_workspace_bytes(0, 4096, 100) == 0
+    assert mb.route_workspace_bytes(32, 4096, 8192) >= 32 * 4096 * 4
+    a = mb.layer_decode_workspace_bytes(32, 4096, 11008, 32)
+    b = mb.layer_decode_workspace_bytes(64, 4096, 11008, 32)
+    assert 0 < a < b
+    assert mb.layer_decode_workspace_bytes(129, 4096, 11008, 32) == 0  # beyond the decode batch limit
+    assert mb.routed_linear_workspace_bytes(32768, 4096, 4096, 32) >= 32768 * 32 * 4
+
+
+def test_argument_validation_happens_before_any_device_work():
+    L = mb.lib()
+    null = ctypes.c_void_p(None)
+    # null tensors
+    assert L.milora_route(null, 10, 8, 0, null, null, null, 1, 1, null, 0, 0, null, null, null, 0, null) == -1
+    ad = mb._Adapters(1, 8, 0, 0, 0)
+    assert L.milora_routed_linear(null, 1, 8, 8, 0, null, null, 0, null, ctypes.byref(ad), 0, null, null, 1, null,
+                                  null, 0, null) == -1
+    lw = mb._LayerWeights()
+    assert L.milora_layer_decode(null, 1, 8, 8, 0, ctypes.byref(lw), ctypes.byref(ad), null, null, 0, null, null,
+                                 null, null, 0, null) == -1
+    assert L.milora_pack_weight(null, null, 32, 16, null) == -1
+    # fake non-null pointers never get dereferenced on these paths: bad enum, bad site, missing workspace
+    p = ctypes.c_void_p(0x1000)
+    assert L.milora_route(p, 10, 8, 7, p, p, p, 1, 1, p, 0, 0, p, null, p, 1 << 20, null) == -1  # dtype 7
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 2, 0, p, null, p, 1 << 20, null) == -1  # pool 2
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 0, p, null, null, 0, null) == -5  # no workspace
+    ad = mb._Adapters(1, 8, 0x1000, 0x1000, 0x1000)
+    assert L.milora_routed_linear(p, 1, 8, 8, 0, null, p, 0, null, ctypes.byref(ad), 9, p, p, 1, p, p, 1 << 20,
+                                  null) == -1  # site 9
+    assert L.milora_routed_linear(p, 2, 8, 8, 0, null, p, 0, null, ctypes.byref(ad), 0, p, p, 1, p, p, 1 << 20,
+                                  null) == -1  # M != B without a row map
+    ad_big = mb._Adapters(1, 1024, 0x1000, 0x1000, 0x1000)
+    assert L.milora_routed_linear(p, 1, 8, 8, 0, null, p, 0, null, ctypes.byref(ad_big), 0, p, p, 1, p, p, 1 << 20,
+                                  null) == -2  # rank limit
+    assert L.milora_routed_linear(p, 1, 8, 8, 1, null, p, 1, null, ctypes.byref(ad), 0, p, p, 1, p, p, 1 << 20,
+                                  null) == -3  # packed fp32
+    assert L.milora_routed_linear(p, 1, 8, 8, 0, null, p, 0, null, ctypes.byref(ad), 0, p, p, 1, p, null, 0,
+                                  null) == -5
+    for m in range(7):
+        lw.W[m] = 0x1000
+    lw.layout = 1
+    assert L.milora_layer_decode(p, 200, 64, 64, 0, ctypes.byref(lw), ctypes.byref(ad), p, p, 0, null, p, null, p,
+                                 1 << 30, null) == -2  # batch limit
+    assert L.milora_layer_decode(p, 4, 64, 64, 1, ctypes.byref(lw), ctypes.byref(ad), p, p, 0, null, p, null, p,
+                                 1 << 30, null) == -3  # packed fp32
+    assert L.milora_layer_decode(p, 4, 64, 64, 0, ctypes.byref(lw), ctypes.byref(ad), p, p, 8, null, p, null, p,
+                                 1 << 30, null) == -1  # unknown flag
+    assert L.milora_pack_weight(p, p, 33, 16, null) == -3
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+
+    with pytest.raises(ValueError):
+        mb._dev(torch.zeros(4))

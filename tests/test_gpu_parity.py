@@ -1,0 +1,291 @@
+"""GPU-vs-oracle parity of the three entry points, through the C ABI (python -m pytest -m gpu).
+
+Every case draws seeded synthetic inputs once, runs the HIP library on them and the fp64 oracle on
+the same stored values, and compares element by element: routes bit-exact outside the near-tie
+margin, outputs within 1e-5 (fp32) / 2e-2 (bf16) relative error per row.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2410_18035_amd import binding as mb
+from paper_2410_18035_amd import synth
+from tests.util import (TOL, assert_routes_match, assert_rows_close, oracle_adapters, to_f64)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def small(name="s", dtype="bf16", d=256, F=352, T=5, B=7, ranks=(8,), **kw):
+    base = dict(L=1, prompt_len=(3, 40), seed=11)
+    base.update(kw)
+    return synth.Workload(name, dtype, d, F, base.pop("L"), T, B, tuple(ranks), base.pop("prompt_len"), **base)
+
+
+def np_of(t):
+    return synth.as_numpy(t)
+
+
+def device_layer(wl, layer=0, zero_B=False):
+    W = synth.base_weights(wl, layer, DEV)
+    ad = synth.adapters(wl, layer, DEV, zero_B=zero_B)
+    tab = mb.AdapterTable.from_tensors(ad.A, ad.B, ad.rank)
+    return W, ad, tab
+
+
+# ------------------------------------------------------------------------------------------- route
+@pytest.mark.parametrize("cfg", ["toy_fp32"])
+def test_route_toy_config(cfg):
+    wl = synth.CONFIGS[cfg]
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl).to(DEV)
+    route, logits = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, wl.pool, wl.act)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr),
+                       mb.POOL[wl.pool], mb.ACT[wl.act])
+    assert_routes_match(route, ref, wl.torch_dtype, cfg)
+    np.testing.assert_allclose(to_f64(logits), ref.logits, atol=1e-5 * np.abs(ref.logits).max())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pool", ["mean", "last"])
+@pytest.mark.parametrize("act", ["identity", "tanh", "relu", "gelu"])
+@pytest.mark.parametrize("d", [256, 100, 1032])
+def test_route_ragged(dtype, pool, act, d):
+    wl = small(dtype=dtype, d=d, T=6, B=19, prompt_len=(1, 300), pool=pool, act=act, tenants="uniform", seed=d)
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    sl[0] = 1  # a one-token prompt: mean = last = the row
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl).to(DEV)
+    route, logits = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, pool, act)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[pool], mb.ACT[act])
+    excluded = assert_routes_match(route, ref, wl.torch_dtype)
+    assert excluded <= 0.11
+    np.testing.assert_allclose(to_f64(logits), ref.logits, atol=2e-5 * max(1.0, np.abs(ref.logits).max()))
+    # same prompt, same table: the router is deterministic
+    route2, _ = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, pool, act)
+    assert torch.equal(route, route2)
+
+
+def test_route_padded_prompts_and_bad_requests():
+    wl = small(dtype="bf16", d=512, T=4, B=6, prompt_len=(5, 64), pad_to=64, seed=5)
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.numpy(), np_of(Wr), oracle.POOL_MEAN, oracle.ACT_GELU)
+    # poison the padding: the pooler must only see valid rows
+    H2 = H.clone()
+    for b in range(wl.B):
+        H2[ss[b] + sl[b]: (b + 1) * 64] = 1e4
+    route, logits = mb.milora_route(H2, ss.to(DEV), sl.to(DEV), tid.to(DEV), Wr, "mean", "gelu")
+    assert_routes_match(route, ref, torch.bfloat16)
+    # a span that leaves H, a zero length and a tenant id out of range are skipped, the rest untouched
+    ss_bad, sl_bad, tid_bad = ss.clone(), sl.clone(), tid.clone()
+    ss_bad[1] = H.shape[0] - 3
+    sl_bad[1] = 10
+    sl_bad[2] = 0
+    tid_bad[4] = wl.T
+    route_b, logits_b = mb.milora_route(H2, ss_bad.to(DEV), sl_bad.to(DEV), tid_bad.to(DEV), Wr, "mean", "gelu")
+    rb = route_b.cpu().numpy()
+    assert (rb[[1, 2, 4]] == mb.ROUTE_NONE).all() and torch.isnan(logits_b[[1, 2, 4]]).all()
+    assert (rb[[0, 3, 5]] == route.cpu().numpy()[[0, 3, 5]]).all()
+
+
+# ------------------------------------------------------------------------------------------- routed linear
+def _linear_case(wl, site, M=None, with_bias=False, row_to_req=None, w_layout=mb.W_ROWMAJOR, route=None, seed=0):
+    W, ad, tab = device_layer(wl)
+    d1, d2 = synth.site_dims(site, wl.d, wl.F)
+    g = torch.Generator().manual_seed(1000 + seed)
+    M = wl.B if M is None else M
+    X = torch.randn(M, d1, generator=g).to(wl.torch_dtype).to(DEV)
+    tid = synth.tenant_ids(wl)
+    if route is None:
+        route = torch.randint(0, 7, (wl.B,), generator=g).to(torch.uint8)
+        route[:: 2] = site  # make sure the site is exercised
+    bias = (torch.randn(d2, generator=g) * 0.1).to(wl.torch_dtype).to(DEV) if with_bias else None
+    r2r = None if row_to_req is None else row_to_req.to(torch.int32)
+    Wdev = mb.milora_pack_weight(W[site]) if w_layout == mb.W_PACKED else W[site]
+    Y = mb.milora_routed_linear(X, Wdev, tab, site, tid.to(DEV), route.to(DEV),
+                                row_to_req=None if r2r is None else r2r.to(DEV), bias=bias, w_layout=w_layout, d2=d2)
+    ref = oracle.routed_linear(np_of(X), np_of(W[site]), oracle_adapters(ad), site, tid.numpy(), route.numpy(),
+                               row_to_req=None if r2r is None else r2r.numpy(),
+                               bias=None if bias is None else np_of(bias))
+    return Y, ref
+
+
+@pytest.mark.parametrize("site", range(7))
+def test_routed_linear_toy_fp32_all_sites(site):
+    wl = synth.CONFIGS["toy_fp32"]
+    Y, ref = _linear_case(wl, site, with_bias=(site % 2 == 0))
+    assert_rows_close(Y, ref, torch.float32, f"site {site}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_routed_linear_generic_ragged_shapes_and_ranks(dtype):
+    # sizes that are multiples of nothing, ranks with and without vector alignment, several rows per request
+    wl = small(dtype=dtype, d=203, F=331, T=4, B=9, ranks=(3, 8, 17), tenants="uniform", seed=21)
+    g = torch.Generator().manual_seed(3)
+    r2r = torch.randint(0, wl.B, (75,), generator=g)
+    for site in (0, 4, 6):
+        Y, ref = _linear_case(wl, site, M=75, row_to_req=r2r, with_bias=True, seed=site)
+        assert_rows_close(Y, ref, wl.torch_dtype, f"{dtype} site {site}")
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 32, 33, 64, 100, 128])
+def test_routed_linear_packed_batch_sizes(M):
+    wl = small(dtype="bf16", d=512, F=1056, T=6, B=M, ranks=(8, 32, 64), tenants="uniform", seed=M)
+    for site in (1, 5, 6):
+        Y, ref = _linear_case(wl, site, w_layout=mb.W_PACKED, with_bias=(site == 5), seed=site)
+        assert_rows_close(Y, ref, torch.bfloat16, f"M {M} site {site}")
+
+
+def test_routed_linear_packed_unaligned_rank_and_row_map():
+    wl = small(dtype="bf16", d=256, F=352, T=3, B=5, ranks=(5, 12, 16), tenants="uniform", seed=8)
+    g = torch.Generator().manual_seed(4)
+    r2r = torch.randint(0, wl.B, (150,), generator=g)  # more than one 128-row slice
+    for site in (2, 4):
+        Y, ref = _linear_case(wl, site, M=150, row_to_req=r2r, w_layout=mb.W_PACKED, seed=site)
+        assert_rows_close(Y, ref, torch.bfloat16, f"site {site}")
+
+
+def test_zero_B_and_unrouted_requests_are_bitwise_the_base_linear():
+    wl = small(dtype="bf16", d=256, F=352, T=4, B=12, ranks=(16,), seed=9)
+    W, ad, tab = device_layer(wl, zero_B=True)
+    tid = synth.tenant_ids(wl).to(DEV)
+    X = synth.decode_input(wl, 0, DEV)
+    for layout in (mb.W_ROWMAJOR, mb.W_PACKED):
+        Wd = mb.milora_pack_weight(W[0]) if layout == mb.W_PACKED else W[0]
+        routed = mb.milora_routed_linear(X, Wd, tab, 0, tid, torch.zeros(wl.B, dtype=torch.uint8, device=DEV),
+                                         w_layout=layout, d2=wl.d)
+        plain = mb.milora_routed_linear(X, Wd, tab, 0, tid, torch.full((wl.B,), 3, dtype=torch.uint8, device=DEV),
+                                        w_layout=layout, d2=wl.d)
+        assert torch.equal(routed, plain)
+        ref = to_f64(X) @ to_f64(W[0]).T
+        assert_rows_close(plain, ref, torch.bfloat16)
+
+
+@pytest.mark.parametrize("dtype,layout", [("f32", mb.W_ROWMAJOR), ("bf16", mb.W_ROWMAJOR), ("bf16", mb.W_PACKED)])
+def test_small_integer_inputs_are_bit_exact(dtype, layout):
+    """Entries in {-2..2}: every product and partial sum is exact in bf16/fp32/fp64, so no tolerance applies."""
+    d, F, T, B, r = 32, 64, 3, 6, 2
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    rnd = lambda shape, lo, hi, seed: synth.small_int_tensor(shape, lo, hi, tdt, seed, DEV)
+    tid = torch.tensor([0, 1, 2, 2, 1, 0], dtype=torch.int32)
+    for site in (0, 5, 6):
+        d1, d2 = synth.site_dims(site, d, F)
+        W = rnd((d2, d1), -1, 1, 10 + site)
+        A = [[rnd((synth.site_dims(m, d, F)[0], r), -1, 1, 100 + 7 * t + m) for m in range(7)] for t in range(T)]
+        Bm = [[rnd((r, synth.site_dims(m, d, F)[1]), -1, 1, 200 + 7 * t + m) for m in range(7)] for t in range(T)]
+        X = rnd((B, d1), -2, 2, 300 + site)
+        route = torch.tensor([site, (site + 1) % 7, site, site, 3, site], dtype=torch.uint8)
+        tab = mb.AdapterTable.from_tensors(A, Bm, [r] * T)
+        Wd = mb.milora_pack_weight(W) if layout == mb.W_PACKED else W
+        Y = mb.milora_routed_linear(X, Wd, tab, site, tid.to(DEV), route.to(DEV), w_layout=layout, d2=d2)
+        ref = oracle.routed_linear(np_of(X), np_of(W), oracle.Adapters(
+            [[np_of(a) for a in row] for row in A], [[np_of(b) for b in row] for row in Bm], [r] * T),
+            site, tid.numpy(), route.numpy())
+        assert np.abs(ref).max() <= 256  # exactly representable in bf16
+        np.testing.assert_array_equal(to_f64(Y), ref)
+
+
+# ------------------------------------------------------------------------------------------- layer decode
+def _layer_case(wl, rmsnorm, layout, with_attn=False, steps=1, route=None):
+    W, ad, tab = device_layer(wl)
+    Wd = [mb.milora_pack_weight(w) for w in W] if layout == mb.W_PACKED else W
+    tid = synth.tenant_ids(wl)
+    if route is None:
+        g = torch.Generator().manual_seed(77)
+        route = torch.randint(0, 7, (wl.B,), generator=g).to(torch.uint8)
+    Wn, adn = [np_of(w) for w in W], oracle_adapters(ad)
+    worst = 0.0
+    for step in range(steps):
+        x = synth.decode_input(wl, step, DEV)
+        attn = synth.decode_input(wl, 1000 + step, DEV) if with_attn else None
+        route_dev = route.to(DEV)
+        y, qkv = mb.milora_layer_decode(x, Wd, tab, tid.to(DEV), route_dev, wl.F, w_layout=layout, rmsnorm=rmsnorm,
+                                        attn_out=attn)
+        assert torch.equal(route_dev.cpu(), route)  # decode never writes the table
+        y_ref, qkv_ref = oracle.layer_decode(np_of(x), Wn, adn, tid.numpy(), route.numpy(), wl.F,
+                                             flags=oracle.FLAG_RMSNORM if rmsnorm else 0,
+                                             attn_out=None if attn is None else np_of(attn))
+        worst = max(worst, assert_rows_close(qkv, qkv_ref, wl.torch_dtype, f"qkv step {step}"))
+        worst = max(worst, assert_rows_close(y, y_ref, wl.torch_dtype, f"y step {step}"))
+    return worst
+
+
+def test_layer_decode_toy_config_all_steps():
+    wl = synth.CONFIGS["toy_fp32"]
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl).to(DEV)
+    route, _ = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, wl.pool, wl.act)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[wl.pool], mb.ACT[wl.act])
+    assert_routes_match(route, ref, torch.float32)
+    _layer_case(wl, False, mb.W_ROWMAJOR, steps=wl.decode_steps, route=torch.from_numpy(ref.route.copy()))
+
+
+@pytest.mark.parametrize("rmsnorm", [False, True])
+@pytest.mark.parametrize("with_attn", [False, True])
+def test_layer_decode_generic_fp32(rmsnorm, with_attn):
+    wl = small(dtype="f32", d=200, F=328, T=4, B=6, ranks=(4, 8), tenants="uniform", seed=31)
+    _layer_case(wl, rmsnorm, mb.W_ROWMAJOR, with_attn)
+
+
+@pytest.mark.parametrize("B", [4, 16, 32, 48, 64, 128])
+@pytest.mark.parametrize("rmsnorm", [False, True])
+def test_layer_decode_packed_bf16(B, rmsnorm):
+    wl = small(dtype="bf16", d=512, F=1376, T=8, B=B, ranks=(8, 16, 64), tenants="uniform", seed=40 + B)
+    _layer_case(wl, rmsnorm, mb.W_PACKED, with_attn=(B == 16))
+
+
+def test_layer_decode_rowmajor_bf16_matches_too():
+    wl = small(dtype="bf16", d=256, F=352, T=4, B=9, ranks=(8,), tenants="uniform", seed=51)
+    _layer_case(wl, True, mb.W_ROWMAJOR)
+
+
+def test_layer_decode_every_request_on_one_site():
+    # the degenerate route tables: all requests on the same site, and no request routed anywhere
+    wl = small(dtype="bf16", d=256, F=352, T=4, B=20, ranks=(16,), tenants="uniform", seed=52)
+    for site in (0, 3, 4, 6):
+        _layer_case(wl, False, mb.W_PACKED, route=torch.full((wl.B,), site, dtype=torch.uint8))
+    _layer_case(wl, False, mb.W_PACKED, route=torch.full((wl.B,), mb.ROUTE_NONE, dtype=torch.uint8))
+
+
+def test_headline_shape_one_step_full_parity():
+    """LLaMA-2-7B-shaped layer, batch 32, 32 tenants, rank 32, packed weights: the benchmark configuration."""
+    wl = synth.CONFIGS["llama7b_layer_b32"]
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl).to(DEV)
+    route, _ = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, wl.pool, wl.act)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[wl.pool], mb.ACT[wl.act])
+    excluded = assert_routes_match(route, ref, torch.bfloat16, "7B routes")
+    assert excluded <= 0.1
+    worst = _layer_case(wl, False, mb.W_PACKED, steps=1, route=torch.from_numpy(ref.route.copy()))
+    print(f"7B layer: excluded routes {excluded:.3f}, worst row rel err {worst:.3e}")
+
+
+# ------------------------------------------------------------------------------------------- error paths
+def test_argument_errors_are_reported_not_thrown_across_the_abi():
+    wl = small(dtype="bf16", d=256, F=352, T=2, B=4, ranks=(8,))
+    W, ad, tab = device_layer(wl)
+    tid = synth.tenant_ids(wl).to(DEV)
+    route = torch.zeros(wl.B, dtype=torch.uint8, device=DEV)
+    x = synth.decode_input(wl, 0, DEV)
+    with pytest.raises(mb.MiloraError) as e:
+        mb.milora_routed_linear(x, W[0], tab, 7, tid, route)
+    assert e.value.status == -1
+    with pytest.raises(mb.MiloraError) as e:
+        mb.milora_routed_linear(x, W[0], tab, 0, tid, route, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
+    assert e.value.status == -5
+    with pytest.raises(mb.MiloraError) as e:  # packed layout needs d1 % 32 == 0
+        mb.milora_routed_linear(x[:, :200].contiguous(), W[0][:, :200].contiguous().view(-1), tab, 0, tid, route,
+                                w_layout=mb.W_PACKED, d2=256)
+    assert e.value.status == -3
+    big = mb.AdapterTable(tab.rank, tab.A_ptrs, tab.B_ptrs, 512, tab.n_tenants, tab.keep)
+    with pytest.raises(mb.MiloraError) as e:
+        mb.milora_routed_linear(x, W[0], big, 0, tid, route)
+    assert e.value.status == -2
