@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed-LoRA hot path on one MI355X.
+
+Workload (default): a LLaMA-2-7B-shaped layer, bf16, batch 32, 32 tenants with rank-32 adapters at all
+seven sites.  One "step" is one pass of the whole hot path over that batch: the prompt-aware router
+over the 32 prompts of 256 tokens (milora_route, once), then 64 decode steps through the seven routed
+linears (milora_layer_decode) that reuse the cached routes.  Inputs are synthetic, seeded and resident
+in HBM before the timed region.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
+
+
+def algorithmic_bytes(wl, routes, tenant_ids, ranks):
+    """Bytes the method itself must move for one decode layer-step, and for the gate/up launch alone.
+
+    base weights once + A and B of every distinct (tenant, site) some request is routed to + activations.
+    """
+    from paper_2410_18035_amd import synth
+
+    s = 2 if wl.dtype == "bf16" else 4
+    d, F, B = wl.d, wl.F, wl.B
+    base = sum(s * d1 * d2 for d1, d2 in (synth.site_dims(m, d, F) for m in range(7)))
+    pairs = {(int(t), int(m)) for t, m in zip(tenant_ids, routes) if 0 <= int(m) < 7}
+    lora = sum(s * ranks[t] * sum(synth.site_dims(m, d, F)) for t, m in pairs)
+    act = s * B * (10 * d + 3 * F) + B + 4 * B
+    gate_up = 2 * s * d * F + sum(s * ranks[t] * F for t, m in pairs if m in (4, 5)) + s * B * d + s * B * F
+    return {"layer_step": base + lora + act, "base": base, "lora": lora, "act": act, "gate_up_launch": gate_up}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b_layer_b32")
+    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-reps", type=int, default=50)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build runs on a single MI355X and has no multi-GPU path "
+              "(use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2410_18035_amd import binding as mb
+    from paper_2410_18035_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: there is no CPU fallback of the HIP path", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.CONFIGS[args.workload]
+    assert wl.L == 1 and wl.dtype == "bf16", "the benchmark runs the single-layer bf16 configurations"
+    nsteps = wl.decode_steps
+
+    # ---- inputs, resident in HBM -----------------------------------------------------------------
+    W = synth.base_weights(wl, 0, dev)
+    Wp = [mb.milora_pack_weight(w) for w in W]
+    ad = synth.adapters(wl, 0, dev)
+    tab = mb.AdapterTable.from_tensors(ad.A, ad.B, ad.rank)
+    Wr = synth.router_weights(wl, 0, dev)
+    tid_host = synth.tenant_ids(wl)
+    tid = tid_host.to(dev)
+    H, ss_host, sl_host = synth.prompts(wl, 0, dev)
+    ss, sl = ss_host.to(dev), sl_host.to(dev)
+    xs = torch.stack([synth.decode_input(wl, s, dev) for s in range(nsteps)])
+    ys = torch.empty_like(xs)
+    qkv = torch.empty(wl.B, 3 * wl.d, dtype=xs.dtype, device=dev)
+    route = torch.empty(wl.B, dtype=torch.uint8, device=dev)
+    ws_route = torch.empty(mb.route_workspace_bytes(wl.B, wl.d, H.shape[0]), dtype=torch.uint8, device=dev)
+    ws_layer = torch.empty(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, tab.r_max), dtype=torch.uint8, device=dev)
+
+    def hot_path_step():
+        mb.milora_route(H, ss, sl, tid, Wr, wl.pool, wl.act, route_out=route, want_logits=False, workspace=ws_route)
+        for s in range(nsteps):
+            mb.milora_layer_decode(xs[s], Wp, tab, tid, route, wl.F, w_layout=mb.W_PACKED, rmsnorm=wl.rmsnorm,
+                                   y=ys[s], qkv_out=qkv, workspace=ws_layer)
+
+    hot_path_step()
+    torch.cuda.synchronize()
+    run = hot_path_step
+    graph = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            hot_path_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            hot_path_step()
+        run = graph.replay
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_step = wl.B * nsteps
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    # ---- per-launch durations with HIP events on the launch stream -----------------------------
+    route_host = route.cpu().numpy()
+    nbytes = algorithmic_bytes(wl, route_host, tid_host.numpy(), ad.rank)
+    _, _, slot_ms = mb.milora_layer_decode(xs[0], Wp, tab, tid, route, wl.F, w_layout=mb.W_PACKED, rmsnorm=wl.rmsnorm,
+                                           y=ys[0], qkv_out=qkv, workspace=ws_layer, profile_reps=args.profile_reps)
+    # route launches timed with events around the call
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        mb.milora_route(H, ss, sl, tid, Wr, wl.pool, wl.act, route_out=route, want_logits=False, workspace=ws_route)
+    e1.record()
+    torch.cuda.synchronize()
+    route_ms = e0.elapsed_time(e1) / 20
+    dominant_ms = slot_ms[5]
+    achieved = nbytes["gate_up_launch"] / (dominant_ms * 1e-3) / 1e9
+    layer_ms = sum(slot_ms)
+    decode_ms_in_step = (ms_per_step - route_ms) / nsteps
+    roofline = {"bound": "hbm", "kernel": "decode_gemm_kernel (gate+up launch)", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": nbytes["gate_up_launch"], "avg_launch_ms": round(dominant_ms, 5)}
+
+    # ---- the oracle on the host cores, bounded sample ---------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        Wn = [synth.as_numpy(w) for w in W]
+        A, Bm, rank = synth.adapters_as_numpy(ad)
+        adn = oracle.Adapters(A, Bm, rank)
+        Hn, Wrn = synth.as_numpy(H), synth.as_numpy(Wr)
+        t0 = time.perf_counter()
+        ref = oracle.route(Hn, ss_host.numpy(), sl_host.numpy(), tid_host.numpy(), Wrn, mb.POOL[wl.pool], mb.ACT[wl.act])
+        t_route = time.perf_counter() - t0
+        done, t_dec = 0, 0.0
+        while done < nsteps and (done < 1 or t_dec + t_dec / done < 20.0):
+            t0 = time.perf_counter()
+            oracle.layer_decode(synth.as_numpy(xs[done]), Wn, adn, tid_host.numpy(), ref.route, wl.F,
+                                flags=oracle.FLAG_RMSNORM if wl.rmsnorm else 0)
+            t_dec += time.perf_counter() - t0
+            done += 1
+        cpu_step_s = t_route + t_dec / done * nsteps
+        cpu = {"value": round(tokens_per_step / cpu_step_s, 2), "unit": "tokens/s", "cores": oracle.n_threads(),
+               "kind": "oracle",
+               "sample": f"router on all {wl.B} prompts ({t_route:.2f} s) + {done} of the {nsteps} decode steps "
+                         f"({t_dec / done:.2f} s each), all {wl.B} requests; scaled to {nsteps} steps"}
+
+    out = {
+        "metric": "routed-LoRA decode tokens/s (batch 32, 32 tenants) + % HBM roofline",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "shape": "LLaMA-2-7B single layer", "d": wl.d, "ffn": wl.F, "batch": wl.B,
+                   "tenants": wl.T, "rank": wl.ranks[0], "prompt_len": wl.prompt_len[0], "decode_steps": nsteps,
+                   "tokens_per_step": tokens_per_step, "weights": "bf16 packed", "hip_graph": graph is not None},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "layer_step": {"us_in_timed_region": round(decode_ms_in_step * 1e3, 2),
+                       "us_sum_of_launches": round(layer_ms * 1e3, 2),
+                       "algorithmic_bytes": nbytes["layer_step"],
+                       "hbm_frac_in_timed_region": round(nbytes["layer_step"] / (decode_ms_in_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "launch_us": [round(v * 1e3, 2) for v in slot_ms],
+                       "route_call_us": round(route_ms * 1e3, 2)},
+        "tokens_per_s_32_layer_equivalent_extrapolated": round(value / 32, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -177,6 +177,22 @@ int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
                         size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * milora_layer_decode_profile - measurement aid, not part of the method: runs milora_layer_decode
+ * `reps` times on `stream` with a HIP event recorded on that stream after every internal kernel
+ * launch, synchronises, and returns the average duration in milliseconds of each launch in
+ * slot_ms (host, MILORA_PROFILE_SLOTS floats; slots the path does not use stay 0).  Packed layout:
+ * slot 2k is the LoRA shrink launch and slot 2k+1 the weight-streaming launch of dependency level k
+ * (0: q,k,v  1: o  2: gate,up  3: down).  Other layouts: EUNSUPPORTED.  Same arguments and errors as
+ * milora_layer_decode otherwise; creates and destroys HIP events, allocates no device memory.
+ */
+#define MILORA_PROFILE_SLOTS 8
+int milora_layer_decode_profile(const void *x, int B, int d, int F, int dtype,
+                                const milora_layer_weights *weights, const milora_adapters *adapters,
+                                const int32_t *tenant_id, const uint8_t *route, uint32_t flags,
+                                const void *attn_out, void *y, void *qkv_out, void *workspace,
+                                size_t workspace_bytes, void *stream, int reps, float *slot_ms);
+
+/* ------------------------------------------------------------------------------------------------
  * milora_pack_weight - one-time re-ordering of a bf16 base weight from MILORA_W_ROWMAJOR to
  * MILORA_W_PACKED (see milora_wlayout), so that the decode kernels stream it with fully
  * coalesced 1 KiB loads already in matrix-core operand order.  src and dst: device, d1*d2

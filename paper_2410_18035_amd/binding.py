@@ -31,7 +31,7 @@ EXPORTS = (
     "milora_version", "milora_status_string", "milora_last_hip_error",
     "milora_route_workspace_bytes", "milora_route",
     "milora_routed_linear_workspace_bytes", "milora_routed_linear",
-    "milora_layer_decode_workspace_bytes", "milora_layer_decode",
+    "milora_layer_decode_workspace_bytes", "milora_layer_decode", "milora_layer_decode_profile",
     "milora_pack_weight",
 )
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.milora_layer_decode.restype = i32
         L.milora_layer_decode.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(_LayerWeights),
                                           ctypes.POINTER(_Adapters), vp, vp, ctypes.c_uint32, vp, vp, vp, vp, sz, vp]
+        L.milora_layer_decode_profile.restype = i32
+        L.milora_layer_decode_profile.argtypes = L.milora_layer_decode.argtypes + [i32, ctypes.POINTER(ctypes.c_float)]
         L.milora_pack_weight.restype = i32
         L.milora_pack_weight.argtypes = [vp, vp, i32, i32, vp]
         _lib = L
@@ -229,12 +231,17 @@ def layer_decode_workspace_bytes(B: int, d: int, F: int, r_max: int) -> int:
     return int(lib().milora_layer_decode_workspace_bytes(B, d, F, r_max))
 
 
+PROFILE_SLOTS = 8
+
+
 def milora_layer_decode(x: torch.Tensor, weights: Sequence[torch.Tensor], adapters: AdapterTable,
                         tenant_id: torch.Tensor, route: torch.Tensor, F: int, w_layout: int = W_ROWMAJOR,
                         rmsnorm: bool = False, attn_out: Optional[torch.Tensor] = None,
                         y: Optional[torch.Tensor] = None, qkv_out: Optional[torch.Tensor] = None,
-                        want_qkv: bool = True, workspace: Optional[torch.Tensor] = None):
-    """One decode step through the seven routed linears of a layer; returns (y [B,d], qkv [B,3d] or None)."""
+                        want_qkv: bool = True, workspace: Optional[torch.Tensor] = None, profile_reps: int = 0):
+    """One decode step through the seven routed linears of a layer; returns (y [B,d], qkv [B,3d] or None).
+
+    With profile_reps > 0 the call goes to milora_layer_decode_profile and returns (y, qkv, slot_ms)."""
     B, d = x.shape
     if len(weights) != NUM_SITES:
         raise ValueError("seven base weights expected")
@@ -251,10 +258,16 @@ def milora_layer_decode(x: torch.Tensor, weights: Sequence[torch.Tensor], adapte
     if workspace is None:
         workspace = _workspace(layer_decode_workspace_bytes(B, d, F, adapters.r_max), x.device)
     ad = adapters.c_struct()
-    rc = lib().milora_layer_decode(_dev(x), B, d, F, _dtype_code(x), ctypes.byref(lw), ctypes.byref(ad),
-                                   _dev(tenant_id, torch.int32), _dev(route, torch.uint8),
-                                   LAYER_RMSNORM if rmsnorm else 0, _dev(attn_out, x.dtype), _dev(y),
-                                   _dev(qkv_out), _dev(workspace), workspace.numel(), _stream())
+    args = (_dev(x), B, d, F, _dtype_code(x), ctypes.byref(lw), ctypes.byref(ad), _dev(tenant_id, torch.int32),
+            _dev(route, torch.uint8), LAYER_RMSNORM if rmsnorm else 0, _dev(attn_out, x.dtype), _dev(y),
+            _dev(qkv_out), _dev(workspace), workspace.numel(), _stream())
+    if profile_reps > 0:
+        slots = (ctypes.c_float * PROFILE_SLOTS)()
+        rc = lib().milora_layer_decode_profile(*args, profile_reps, slots)
+        if rc != 0:
+            raise MiloraError(rc, "milora_layer_decode_profile")
+        return y, qkv_out, [float(v) for v in slots]
+    rc = lib().milora_layer_decode(*args)
     if rc != 0:
         raise MiloraError(rc, "milora_layer_decode")
     return y, qkv_out

@@ -11,7 +11,7 @@ thread_local int g_last_hip_error = 0;
 size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max);
 int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer_weights* wts, const AdapterView& ad,
                         const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
-                        bf16_t* y, bf16_t* qkv_out, void* workspace, hipStream_t st);
+                        bf16_t* y, bf16_t* qkv_out, void* workspace, hipStream_t st, LaunchMarks* marks);
 int routed_linear_packed(const bf16_t* X, int M, int d1, int d2, const int32_t* row_to_req, const bf16_t* W,
                          const bf16_t* bias, const AdapterView& ad, int site, const int32_t* tenant_id,
                          const uint8_t* route, int B, bf16_t* Y, void* workspace, hipStream_t st);
@@ -262,10 +262,10 @@ extern "C" size_t milora_layer_decode_workspace_bytes(int B, int d, int F, int r
   return a > b ? a : b;
 }
 
-extern "C" int milora_layer_decode(const void* x, int B, int d, int F, int dtype, const milora_layer_weights* weights,
-                                   const milora_adapters* adapters, const int32_t* tenant_id, const uint8_t* route,
-                                   uint32_t flags, const void* attn_out, void* y, void* qkv_out, void* workspace,
-                                   size_t workspace_bytes, void* stream) {
+static int layer_decode_impl(const void* x, int B, int d, int F, int dtype, const milora_layer_weights* weights,
+                             const milora_adapters* adapters, const int32_t* tenant_id, const uint8_t* route,
+                             uint32_t flags, const void* attn_out, void* y, void* qkv_out, void* workspace,
+                             size_t workspace_bytes, void* stream, LaunchMarks* marks) {
   if (!x || !y || !weights || !tenant_id || !route) return MILORA_EINVAL;
   if (B < 1 || d < 1 || F < 1 || !valid_dtype(dtype)) return MILORA_EINVAL;
   if (flags & ~MILORA_LAYER_RMSNORM) return MILORA_EINVAL;
@@ -286,13 +286,50 @@ extern "C" int milora_layer_decode(const void* x, int B, int d, int F, int dtype
     for (int m = 0; m < MILORA_NUM_SITES; ++m)
       if (!aligned16(weights->W[m])) return MILORA_EUNSUPPORTED;
     return layer_decode_packed((const bf16_t*)x, B, d, F, weights, ad, tenant_id, route, flags,
-                               (const bf16_t*)attn_out, (bf16_t*)y, (bf16_t*)qkv_out, workspace, st);
+                               (const bf16_t*)attn_out, (bf16_t*)y, (bf16_t*)qkv_out, workspace, st, marks);
   }
+  if (marks) return MILORA_EUNSUPPORTED;
   if (dtype == MILORA_BF16)
     return layer_decode_generic<bf16_t>(x, B, d, F, dtype, weights, ad, tenant_id, route, flags, attn_out, y, qkv_out,
                                         workspace, st);
   return layer_decode_generic<float>(x, B, d, F, dtype, weights, ad, tenant_id, route, flags, attn_out, y, qkv_out,
                                      workspace, st);
+}
+
+extern "C" int milora_layer_decode(const void* x, int B, int d, int F, int dtype, const milora_layer_weights* weights,
+                                   const milora_adapters* adapters, const int32_t* tenant_id, const uint8_t* route,
+                                   uint32_t flags, const void* attn_out, void* y, void* qkv_out, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  return layer_decode_impl(x, B, d, F, dtype, weights, adapters, tenant_id, route, flags, attn_out, y, qkv_out,
+                           workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int milora_layer_decode_profile(const void* x, int B, int d, int F, int dtype,
+                                           const milora_layer_weights* weights, const milora_adapters* adapters,
+                                           const int32_t* tenant_id, const uint8_t* route, uint32_t flags,
+                                           const void* attn_out, void* y, void* qkv_out, void* workspace,
+                                           size_t workspace_bytes, void* stream, int reps, float* slot_ms) {
+  if (!slot_ms || reps < 1) return MILORA_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t ev[MILORA_PROFILE_SLOTS + 1];
+  for (int i = 0; i <= MILORA_PROFILE_SLOTS; ++i) MILORA_HIP(hipEventCreate(&ev[i]));
+  for (int i = 0; i < MILORA_PROFILE_SLOTS; ++i) slot_ms[i] = 0.f;
+  LaunchMarks marks{ev + 1, MILORA_PROFILE_SLOTS};
+  int rc = MILORA_OK;
+  for (int r = 0; r < reps && rc == MILORA_OK; ++r) {
+    MILORA_HIP(hipEventRecord(ev[0], st));
+    rc = layer_decode_impl(x, B, d, F, dtype, weights, adapters, tenant_id, route, flags, attn_out, y, qkv_out,
+                           workspace, workspace_bytes, stream, &marks);
+    if (rc != MILORA_OK) break;
+    MILORA_HIP(hipStreamSynchronize(st));
+    for (int i = 0; i < MILORA_PROFILE_SLOTS; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) == hipSuccess) slot_ms[i] += ms / (float)reps;
+      else (void)hipGetLastError();
+    }
+  }
+  for (int i = 0; i <= MILORA_PROFILE_SLOTS; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
 }
 
 extern "C" int milora_pack_weight(const void* src_rowmajor, void* dst_packed, int d1, int d2, void* stream) {

@@ -93,6 +93,12 @@ __device__ __forceinline__ int routed_rank(const AdapterView& ad, const int32_t*
   return r;
 }
 
+// Optional per-launch event marks of the packed layer path (measurement only).
+struct LaunchMarks {
+  hipEvent_t* ev;
+  int n;
+};
+
 // ---- internal entry points shared between translation units ------------------------------------
 // LoRA shrink: for every row m whose request is routed to `site`, t[m][0..r) = X[m] . A (fp32).
 // t is [M][r_max] floats; rows that carry no LoRA term are left untouched.

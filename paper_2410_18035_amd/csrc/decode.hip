@@ -495,11 +495,15 @@ static void clear_epilogue(GemmParams& p) {
 }
 
 // One decode step of a layer on packed weights: four dependency levels, each a shrink launch for the
-// rows routed to that level's sites followed by one weight-streaming launch.
+// rows routed to that level's sites followed by one weight-streaming launch.  With `marks`, an event is
+// recorded after every launch (slot order: shrink, gemm of level 0, 1, 2, 3).
 int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer_weights* wts, const AdapterView& ad,
                         const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
-                        bf16_t* y, bf16_t* qkv_out, void* workspace, hipStream_t st) {
+                        bf16_t* y, bf16_t* qkv_out, void* workspace, hipStream_t st, LaunchMarks* marks) {
   const int MT = mt_for(B);
+  auto mark = [&](int slot) {
+    if (marks && slot < marks->n) (void)hipEventRecord(marks->ev[slot], st);
+  };
   DecodeWs ws = carve_decode_ws(workspace, B, d, F, ad.r_max);
   const int norm = (flags & MILORA_LAYER_RMSNORM) ? 1 : 0;
   GemmParams p;
@@ -515,6 +519,7 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     const int sites[3] = {0, 1, 2};
     rc = launch_decode_shrink(x, false, MT, d, B, B, ad, 3, sites, tenant_id, route, nullptr, shrink_chunks(d), ws.tpart, st);
     if (rc) return rc;
+    mark(0);
     common(x, d);
     p.n_sites = 3; p.norm = norm;
     for (int s = 0; s < 3; ++s) {
@@ -525,6 +530,7 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     if (!attn_out) p.out_pk[2] = ws.pk_a;
     rc = launch_gemm(p, MT, false, st);
     if (rc) return rc;
+    mark(1);
   }
   // level 1: h = x + L_o(a)
   {
@@ -543,6 +549,7 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     const int sites[1] = {3};
     rc = launch_decode_shrink(a_in, true, MT, d, B, B, ad, 1, sites, tenant_id, route, nullptr, shrink_chunks(d), ws.tpart, st);
     if (rc) return rc;
+    mark(2);
     common(a_in, d);
     p.n_sites = 1;
     p.W[0] = (const bf16_t*)wts->W[3]; p.N[0] = d; p.site[0] = 3; p.tile_end[0] = d / 16;
@@ -552,12 +559,14 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     p.out_pk[0] = ws.pk_b;
     rc = launch_gemm(p, MT, true, st);
     if (rc) return rc;
+    mark(3);
   }
   // level 2: m = silu(L_gate(n(h))) * L_up(n(h))
   {
     const int sites[2] = {4, 5};
     rc = launch_decode_shrink(ws.pk_b, true, MT, d, B, B, ad, 2, sites, tenant_id, route, nullptr, shrink_chunks(d), ws.tpart, st);
     if (rc) return rc;
+    mark(4);
     common(ws.pk_b, d);
     p.n_sites = 2; p.pair = 1; p.silu_mul = 1; p.norm = norm;
     for (int s = 0; s < 2; ++s) { p.W[s] = (const bf16_t*)wts->W[4 + s]; p.N[s] = F; p.site[s] = 4 + s; }
@@ -565,12 +574,14 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     p.out_pk[0] = ws.pk_a;
     rc = launch_gemm(p, MT, true, st);
     if (rc) return rc;
+    mark(5);
   }
   // level 3: y = h + L_down(m)
   {
     const int sites[1] = {6};
     rc = launch_decode_shrink(ws.pk_a, true, MT, F, B, B, ad, 1, sites, tenant_id, route, nullptr, shrink_chunks(F), ws.tpart, st);
     if (rc) return rc;
+    mark(6);
     common(ws.pk_a, F);
     p.n_sites = 1;
     p.W[0] = (const bf16_t*)wts->W[6]; p.N[0] = d; p.site[0] = 6; p.tile_end[0] = d / 16;
@@ -578,6 +589,7 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     p.out_rm[0] = y; p.ld_rm = d; p.col_off[0] = 0;
     rc = launch_gemm(p, MT, true, st);
     if (rc) return rc;
+    mark(7);
   }
   return MILORA_OK;
 }
