@@ -68,7 +68,7 @@ __device__ __forceinline__ float sumsq8(u32x4 v) {
   return s;
 }
 
-template <int MT, int NACC, int NW, int D, bool XPACKED>
+template <int MT, int NACC, int NW, int D, bool XPACKED, bool NORM>
 __global__ void __launch_bounds__(NW * 64) decode_gemm_kernel(const GemmParams p) {
   constexpr int kThreads = NW * 64;
   constexpr int kRedSlots = NW / 2 > 0 ? NW / 2 : 1;
@@ -78,7 +78,8 @@ __global__ void __launch_bounds__(NW * 64) decode_gemm_kernel(const GemmParams p
   __shared__ int l_m[kMaxRows], l_r[kMaxRows], l_t[kMaxRows], l_a[kMaxRows];
   __shared__ int l_cnt;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, kept in a scalar register
   int si = 0, j = blockIdx.x;
   if (!p.pair) {
     while (si + 1 < p.n_sites && j >= p.tile_end[si]) ++si;
@@ -128,27 +129,39 @@ __global__ void __launch_bounds__(NW * 64) decode_gemm_kernel(const GemmParams p
 #pragma unroll
       for (int a = 0; a < NACC; ++a)
         acc[a][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wb[s][a]), xv, acc[a][mt], 0, 0, 0);
-      if (p.norm) ss[mt] += sumsq8(xb[s][mt]);
+      if (NORM) ss[mt] += sumsq8(xb[s][mt]);
     }
   };
+  if (nf >= 2 * D) {
+    // Register ring of D blocks per stream.  The fill and the steady loop issue unconditionally, so the
+    // number of loads in flight is the same on every path into a consume and the compiler can wait for
+    // the oldest block only.
 #pragma unroll
-  for (int s = 0; s < D; ++s)
-    if (s < nf) issue(s, s);
-  int i0 = 0;
-  for (; i0 + 2 * D <= nf; i0 += D) {
+    for (int s = 0; s < D; ++s) {
+      issue(s, s);
+      __builtin_amdgcn_sched_barrier(0);  // the fill must reach memory oldest block first
+    }
+    int i0 = 0;
+    for (; i0 + 2 * D <= nf; i0 += D) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) {
+        consume(s);
+        issue(s, i0 + D + s);
+        __builtin_amdgcn_sched_barrier(0);  // keep the refill next to its consume: no batching of the loads
+      }
+    }
 #pragma unroll
     for (int s = 0; s < D; ++s) {
       consume(s);
-      issue(s, i0 + D + s);
+      if (i0 + D + s < nf) issue(s, i0 + D + s);
     }
-  }
-  for (; i0 < nf; i0 += D) {
 #pragma unroll
-    for (int s = 0; s < D; ++s) {
-      if (i0 + s < nf) {
-        consume(s);
-        if (i0 + D + s < nf) issue(s, i0 + D + s);
-      }
+    for (int s = 0; s < D; ++s)
+      if (i0 + D + s < nf) consume(s);
+  } else {
+    for (int i = 0; i < nf; ++i) {  // short reductions: no ring
+      issue(0, i);
+      consume(0);
     }
   }
 
@@ -183,7 +196,7 @@ __global__ void __launch_bounds__(NW * 64) decode_gemm_kernel(const GemmParams p
 #pragma unroll
         for (int i = 0; i < 4; ++i) red[red_idx(0, a, mt, i, lane)] = acc[a][mt][i];
   }
-  if (p.norm) {
+  if (NORM) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       float v = ss[mt];
@@ -261,7 +274,7 @@ __global__ void __launch_bounds__(NW * 64) decode_gemm_kernel(const GemmParams p
   for (int m = tid >> 3; m < p.M; m += kThreads / 8) {
     const int mt = m >> 4;
     float inv = 1.f;
-    if (p.norm) {
+    if (NORM) {
       float s = 0.f;
       for (int ww = 0; ww < NW; ++ww) s += ssq_s[(ww * MT + mt) * 16 + (m & 15)];
       inv = rsqrtf(s / (float)p.K + 1e-5f);
@@ -415,7 +428,8 @@ template <int MT, int NACC, bool XPACKED>
 void launch_gemm_t(const GemmParams& p, int tiles, hipStream_t st) {
   constexpr int NW = 4;
   constexpr int D = MT <= 2 ? 8 : (MT == 4 ? 6 : 4);
-  hipLaunchKernelGGL((decode_gemm_kernel<MT, NACC, NW, D, XPACKED>), dim3(tiles), dim3(NW * 64), 0, st, p);
+  if (p.norm) hipLaunchKernelGGL((decode_gemm_kernel<MT, NACC, NW, D, XPACKED, true>), dim3(tiles), dim3(NW * 64), 0, st, p);
+  else hipLaunchKernelGGL((decode_gemm_kernel<MT, NACC, NW, D, XPACKED, false>), dim3(tiles), dim3(NW * 64), 0, st, p);
 }
 
 template <int MT>

@@ -241,6 +241,14 @@ def test_layer_decode_packed_bf16(B, rmsnorm):
     _layer_case(wl, rmsnorm, mb.W_PACKED, with_attn=(B == 16))
 
 
+@pytest.mark.parametrize("B", [8, 40])
+def test_layer_decode_packed_long_ragged_reduction(B):
+    # reduction lengths whose per-wave block counts are long enough for the register ring and not a
+    # multiple of its depth (65 and 73 blocks of 32 over four waves)
+    wl = small(dtype="bf16", d=2080, F=2336, T=4, B=B, ranks=(16, 32), tenants="uniform", seed=60 + B)
+    _layer_case(wl, True, mb.W_PACKED)
+
+
 def test_layer_decode_rowmajor_bf16_matches_too():
     wl = small(dtype="bf16", d=256, F=352, T=4, B=9, ranks=(8,), tenants="uniform", seed=51)
     _layer_case(wl, True, mb.W_ROWMAJOR)
