@@ -15,7 +15,7 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
 int routed_linear_packed(const bf16_t* X, int M, int d1, int d2, const int32_t* row_to_req, const bf16_t* W,
                          const bf16_t* bias, const AdapterView& ad, int site, const int32_t* tenant_id,
                          const uint8_t* route, int B, bf16_t* Y, void* workspace, hipStream_t st);
-size_t routed_linear_packed_workspace_bytes(int M, int d1, int r_max);
+size_t routed_linear_packed_workspace_bytes(int M, int d1, int d2, int r_max);
 int pack_weight(const void* src, void* dst, int d1, int d2, hipStream_t st);
 // prefill.hip
 bool prefill_supported(int64_t M, int d1, int d2, const void* X, const void* W, const void* Y);
@@ -208,11 +208,10 @@ extern "C" const char* milora_status_string(int status) {
 extern "C" int milora_last_hip_error(void) { return g_last_hip_error; }
 
 extern "C" size_t milora_routed_linear_workspace_bytes(int64_t M, int d1, int d2, int r_max) {
-  (void)d2;
-  if (M < 1 || d1 < 1 || r_max < 1) return 0;
+  if (M < 1 || d1 < 1 || d2 < 1 || r_max < 1) return 0;
   size_t generic = align_up((size_t)M * r_max * sizeof(float), 256);
-  size_t packed = M <= MILORA_MAX_DECODE_BATCH ? routed_linear_packed_workspace_bytes((int)M, d1, r_max)
-                                               : routed_linear_packed_workspace_bytes(MILORA_MAX_DECODE_BATCH, d1, r_max);
+  const int mp = M <= MILORA_MAX_DECODE_BATCH ? (int)M : MILORA_MAX_DECODE_BATCH;
+  size_t packed = routed_linear_packed_workspace_bytes(mp, d1, d2, r_max);
   return generic > packed ? generic : packed;
 }
 

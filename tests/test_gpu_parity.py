@@ -142,6 +142,17 @@ def test_routed_linear_packed_batch_sizes(M):
         assert_rows_close(Y, ref, torch.bfloat16, f"M {M} site {site}")
 
 
+@pytest.mark.parametrize("d,F,site,M", [(4096, 64, 4, 20), (64, 11008, 6, 32), (2560, 96, 5, 70), (4096, 64, 0, 128)])
+def test_routed_linear_packed_sliced_reduction(d, F, site, M):
+    """Few output columns and a long reduction: the reduction is cut into slices handled by different
+    workgroups and summed by the last one to finish (4, 10, 2 and 4 slices here)."""
+    wl = small(dtype="bf16", d=d, F=F, T=5, B=M, ranks=(8, 32), tenants="uniform", seed=d + F)
+    Y, ref = _linear_case(wl, site, w_layout=mb.W_PACKED, with_bias=True, seed=M)
+    assert_rows_close(Y, ref, torch.bfloat16, f"d {d} F {F} site {site}")
+    Y2, _ = _linear_case(wl, site, w_layout=mb.W_PACKED, with_bias=True, seed=M)
+    assert torch.equal(Y, Y2)  # fixed summation order: bitwise repeatable
+
+
 def test_routed_linear_packed_unaligned_rank_and_row_map():
     wl = small(dtype="bf16", d=256, F=352, T=3, B=5, ranks=(5, 12, 16), tenants="uniform", seed=8)
     g = torch.Generator().manual_seed(4)
