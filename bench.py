@@ -131,13 +131,13 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     route_ms = e0.elapsed_time(e1) / 20
-    dominant_ms = slot_ms[3]  # the gate+up level launch
-    achieved = nbytes["gate_up_launch"] / (dominant_ms * 1e-3) / 1e9
+    dominant_ms = slot_ms[1]  # the persistent launch that walks the four levels of the layer
+    achieved = nbytes["layer_step"] / (dominant_ms * 1e-3) / 1e9
     layer_ms = sum(slot_ms)
     decode_ms_in_step = (ms_per_step - route_ms) / nsteps
-    roofline = {"bound": "hbm", "kernel": "decode_level_kernel (gate+up launch)", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": "decode_persist_kernel (one decode step of the layer)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "algorithmic_bytes_per_launch": nbytes["gate_up_launch"], "avg_launch_ms": round(dominant_ms, 5)}
+                "algorithmic_bytes_per_launch": nbytes["layer_step"], "avg_launch_ms": round(dominant_ms, 5)}
 
     # ---- the oracle on the host cores, bounded sample ---------------------------------------------
     cpu = None

@@ -181,8 +181,9 @@ int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
  * `reps` times on `stream` with a HIP event recorded on that stream after every internal kernel
  * launch, synchronises, and returns the average duration in milliseconds of each launch in
  * slot_ms (host, MILORA_PROFILE_SLOTS floats; slots the path does not use stay 0).  Packed layout:
- * slot 0 is the counter-clearing launch, slots 1..4 the launches of dependency levels 0..3
- * (q,k,v | o | gate,up | down).  Other layouts: EUNSUPPORTED.  Same arguments and errors as
+ * slot 0 is the preparation launch (counters zeroed, x re-ordered into matrix-core operand blocks) and
+ * slot 1 the persistent launch that walks the four dependency levels q,k,v | o | gate,up | down.
+ * Other layouts: EUNSUPPORTED.  Same arguments and errors as
  * milora_layer_decode otherwise; creates and destroys HIP events, allocates no device memory.
  */
 #define MILORA_PROFILE_SLOTS 8
