@@ -82,7 +82,7 @@ def main():
     qkv = torch.empty(wl.B, 3 * wl.d, dtype=xs.dtype, device=dev)
     route = torch.empty(wl.B, dtype=torch.uint8, device=dev)
     ws_route = torch.empty(mb.route_workspace_bytes(wl.B, wl.d, H.shape[0]), dtype=torch.uint8, device=dev)
-    ws_layer = torch.empty(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, tab.r_max), dtype=torch.uint8, device=dev)
+    ws_layer = torch.zeros(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, tab.r_max), dtype=torch.uint8, device=dev)
 
     def hot_path_step():
         mb.milora_route(H, ss, sl, tid, Wr, wl.pool, wl.act, route_out=route, want_logits=False, workspace=ws_route)
@@ -131,11 +131,11 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     route_ms = e0.elapsed_time(e1) / 20
-    dominant_ms = slot_ms[1]  # the persistent launch that walks the four levels of the layer
+    dominant_ms = slot_ms[0]  # the one launch that walks the four stages of the layer
     achieved = nbytes["layer_step"] / (dominant_ms * 1e-3) / 1e9
     layer_ms = sum(slot_ms)
     decode_ms_in_step = (ms_per_step - route_ms) / nsteps
-    roofline = {"bound": "hbm", "kernel": "decode_persist_kernel (one decode step of the layer)", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": "decode_stream_kernel (one decode step of the layer)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "algorithmic_bytes_per_launch": nbytes["layer_step"], "avg_launch_ms": round(dominant_ms, 5)}
 

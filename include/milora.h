@@ -14,8 +14,12 @@
  *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
  *    and the call returns without synchronising.  Buffers must stay valid until that work is done.
  *  - The library allocates nothing.  Calls that need scratch memory take a device `workspace`
- *    of at least the size the matching *_workspace_bytes() function returns; its contents are
- *    undefined afterwards.  Two calls that share a workspace must be ordered on one stream.
+ *    of at least the size the matching *_workspace_bytes() function returns.  A workspace must be
+ *    zero-filled once before its first use: the decode kernels keep their cross-workgroup
+ *    hand-over flags in it, as values that only grow from launch to launch, so nothing has to be
+ *    cleared between calls; apart from that its contents are undefined.  After a call that
+ *    returned an error, or when the same memory is to serve another entry point or other sizes,
+ *    zero it again.  Two calls that share a workspace must be ordered on one stream.
  *  - Return value: MILORA_OK (0) or a negative milora_status.  Arguments are validated on the
  *    host before anything is enqueued; values that live in device arrays (tenant ids, routes,
  *    prompt spans) are checked by the kernels, which then skip the offending request as
@@ -136,8 +140,8 @@ int milora_route(const void *H, int64_t M_tok, int d, int dtype, const int32_t *
  *   Y           device [M][d2], `dtype`
  *   workspace   device, milora_routed_linear_workspace_bytes(M, d1, d2, r_max) bytes
  * A row whose request index, tenant id or tenant rank is out of range gets the base term only.
- * Errors: EINVAL, ERANGE (r_max > MILORA_MAX_RANK), EUNSUPPORTED (packed layout with fp32 or with
- * d1 % 32 != 0 or d2 % 16 != 0), EWORKSPACE, EHIP.
+ * Errors: EINVAL, ERANGE (r_max > MILORA_MAX_RANK), EUNSUPPORTED (packed layout with fp32, with
+ * d1 % 32 != 0 or d2 % 16 != 0, or with X, W, bias or Y not 16-byte aligned), EWORKSPACE, EHIP.
  */
 size_t milora_routed_linear_workspace_bytes(int64_t M, int d1, int d2, int r_max);
 int milora_routed_linear(const void *X, int64_t M, int d1, int d2, int dtype,
@@ -167,7 +171,8 @@ int milora_routed_linear(const void *X, int64_t M, int d1, int d2, int dtype,
  *   qkv_out   device [B][3d] `dtype` or NULL: q | k | v of every request, for the caller's attention
  *   workspace device, milora_layer_decode_workspace_bytes(B, d, F, r_max) bytes
  * Errors: EINVAL, ERANGE (B > MILORA_MAX_DECODE_BATCH, r_max > MILORA_MAX_RANK), EUNSUPPORTED
- * (packed layout with fp32 or unaligned d, F), EWORKSPACE, EHIP.
+ * (packed layout with fp32, with d or F not a multiple of 32, or with x, y, attn_out, qkv_out or a
+ * weight not 16-byte aligned), EWORKSPACE, EHIP.
  */
 size_t milora_layer_decode_workspace_bytes(int B, int d, int F, int r_max);
 int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
@@ -181,8 +186,7 @@ int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
  * `reps` times on `stream` with a HIP event recorded on that stream after every internal kernel
  * launch, synchronises, and returns the average duration in milliseconds of each launch in
  * slot_ms (host, MILORA_PROFILE_SLOTS floats; slots the path does not use stay 0).  Packed layout:
- * slot 0 is the preparation launch (counters zeroed, x re-ordered into matrix-core operand blocks) and
- * slot 1 the persistent launch that walks the four dependency levels q,k,v | o | gate,up | down.
+ * the whole decode step is one launch that walks q,k,v | o | gate,up | down, timed in slot 0.
  * Other layouts: EUNSUPPORTED.  Same arguments and errors as
  * milora_layer_decode otherwise; creates and destroys HIP events, allocates no device memory.
  */

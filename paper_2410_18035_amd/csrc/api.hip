@@ -232,7 +232,8 @@ extern "C" int milora_routed_linear(const void* X, int64_t M, int d1, int d2, in
   hipStream_t st = (hipStream_t)stream;
   const AdapterView ad = view_of(adapters);
   if (w_layout == MILORA_W_PACKED) {
-    if (dtype != MILORA_BF16 || !packed_shape_ok(d1, d2) || !aligned16(X) || !aligned16(W) || ((uintptr_t)Y & 3))
+    if (dtype != MILORA_BF16 || !packed_shape_ok(d1, d2) || !aligned16(X) || !aligned16(W) || !aligned16(Y) ||
+        (bias && !aligned16(bias)))
       return MILORA_EUNSUPPORTED;
     if (!row_to_req && M > MILORA_MAX_DECODE_BATCH) return MILORA_ERANGE;
     // rows are independent: larger M runs as slices of at most 128 rows (each re-reads W)
@@ -280,7 +281,7 @@ static int layer_decode_impl(const void* x, int B, int d, int F, int dtype, cons
   const AdapterView ad = view_of(adapters);
   if (weights->layout == MILORA_W_PACKED) {
     if (dtype != MILORA_BF16 || d % 32 != 0 || F % 32 != 0) return MILORA_EUNSUPPORTED;
-    if (!aligned16(x) || (attn_out && !aligned16(attn_out)) || ((uintptr_t)y & 3) || ((uintptr_t)qkv_out & 3))
+    if (!aligned16(x) || (attn_out && !aligned16(attn_out)) || !aligned16(y) || (qkv_out && !aligned16(qkv_out)))
       return MILORA_EUNSUPPORTED;
     for (int m = 0; m < MILORA_NUM_SITES; ++m)
       if (!aligned16(weights->W[m])) return MILORA_EUNSUPPORTED;

@@ -1,30 +1,27 @@
 // Decode-time routed LoRA linears on packed bf16 weights (paper Eq. 1; Sec. 3.3 route reuse).
 //
 // At decode the batch is skinny (B <= 128 rows) and every base weight is read exactly once per
-// step, so everything is built around keeping the HBM stream of W running on all 256 CUs.  Weights
-// are pre-packed in 1 KiB blocks that already are 16x16x32 matrix-core operands (one wave load =
-// one contiguous block).  A whole decode step of a layer is one persistent launch of G = 256 k
-// workgroups that walks the four dependency levels (q,k,v | o | gate,up | down) with a grid barrier
-// between levels.  Inside a level every workgroup
-//   1. takes its share of the LoRA shrink items (routed row x 512-row chunk of A): partial
-//      t = x[chunk] . A[chunk]; the workgroup that delivers a row's last partial sums them in
-//      chunk order and publishes the row's t;
-//   2. takes an equal share of the level's weight blocks: the level is the list of (column group of
-//      four 16-column tiles, k block) units and workgroup i owns units [iU/G, (i+1)U/G), so a share
-//      is one or two runs inside a column group ("segments").  The four waves interleave along k;
-//      the batch rows ride in the other MFMA operand and are loaded once per k block for all four
-//      tiles; a register ring keeps D blocks per stream in flight;
-//   3. for each segment reduces the waves' partial tiles through LDS; a group whose k range is
-//      split over several workgroups is summed, in workgroup order, by whichever of them finishes
-//      last; that workgroup adds the LoRA expand t W^B of the routed rows in fp32, applies the layer
-//      glue (normalisation scale, residual, silu*up) and rounds once to bf16.
-// Data handed from one workgroup to another (partials, t, the activations of the next level) is
-// written with agent-scope stores, which go through to memory that all XCDs share instead of
-// staying in one XCD's L2; partials and t are also read with agent-scope loads.  A producer waits
-// for its own stores, passes a workgroup barrier and bumps an agent-scope counter; a consumer reads
-// the counter before the data.  Activation buffers are distinct per level, so no XCD can hold a
-// stale line of them.  Every wait is bounded, and all sums run in a fixed order: results do not
-// depend on timing.
+// step, so everything is built around never letting the HBM stream of W stop.  Weights are
+// pre-packed in 1 KiB blocks that already are 16x16x32 matrix-core operands (one wave load = one
+// contiguous block).  A whole decode step of a layer is ONE launch of one workgroup per compute
+// unit that walks the stages q,k,v | o | gate,up | down.  A workgroup has three kinds of waves:
+//   * stream waves: each owns every kSW-th 32-input block of the workgroup's 16-column tiles and
+//     keeps a ring of kD weight blocks in registers.  The ring is refilled in stage order without
+//     regard to stage boundaries: weights do not depend on activations, so while a stage ends
+//     (reduction, LoRA expand, stores, grid barrier, first inputs of the next stage) the loads of the
+//     next stage's weights are already in flight and HBM stays busy.
+//   * one loader wave: moves the stage input (row-major bf16 rows) through L2 into LDS in
+//     matrix-core operand order, chunk by chunk, ahead of the stream waves.  It has its own
+//     memory counter, so waiting for these late-issued loads does not drain the weight ring.
+//   * one LoRA wave: forms partial shrinks t = x[chunk] . A[chunk] of routed rows, the wave that
+//     delivers a row's last partial sums them in chunk order and publishes t.
+// Stage end: the stream waves' partial tiles are summed in wave order through LDS, the LoRA expand
+// t W^B of the routed rows is added in fp32, the layer glue (normalisation scale, residual,
+// silu*up) applied, one rounding to bf16.  Stages that depend on each other are separated by a
+// grid barrier of per-workgroup flags (monotone values, nothing to reset between launches).
+// All sums run in a fixed order: results do not depend on timing.
+#include <type_traits>
+
 #include "common.h"
 
 namespace milora {
@@ -33,89 +30,146 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) u32x4 gu32x4;  // in global memory: loads count on the vector-memory counter only
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
-constexpr int kNT = 4;              // 16-column tiles (weight streams) per column group
-constexpr int kShrinkChunk = 512;   // reduction rows per LoRA shrink item
+constexpr int kSW = 6;                  // stream waves per workgroup
+constexpr int kLoader = kSW;            // wave index of the input loader
+constexpr int kLora = kSW + 1;          // wave index of the LoRA wave
+constexpr int kWaves = kSW + 2;
+constexpr int kThreads = kWaves * 64;
+constexpr int kMaxStages = 12;
 constexpr int kMaxRows = MILORA_MAX_DECODE_BATCH;
-constexpr int kMaxGroups = 2048;    // column groups per level the counters are sized for
-constexpr int kMaxLevels = 4;
-constexpr int kSpinLimit = 1 << 20; // polls of a counter before a workgroup stops waiting
-constexpr int kCntPerLevel = 3 * kMaxRows + kMaxGroups;
-constexpr int kSync = kMaxLevels * kCntPerLevel + 64;  // ints of the synchronisation block (+ barrier word, status)
+constexpr int kMaxGrid = 1024;          // workgroups the barrier flags are sized for
+constexpr int kShrinkChunk = 512;       // reduction rows per LoRA shrink item
+constexpr int kSteady = 8;              // weight loads per stream wave in flight between stage ends
+constexpr int kSpinLimit = 1 << 22;     // polls before a bounded wait gives up
+constexpr int kCtrlBytes = 12288;       // control block at the start of LDS
+constexpr int kXRegionBytes = 144 * 1024;  // input chunks; re-used for the stage-end reduction
 
-// Offset (in bf16 elements) of activation element (row m, feature k) in a block-packed buffer of MT row tiles.
-__device__ __host__ __forceinline__ size_t packed_act_offset(int m, int k, int MT) {
-  return ((((size_t)(k >> 5) * MT + (m >> 4)) * 64) + (m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
-}
+// Per row-tile-count tuning: ring depth, tiles per workgroup and stage.
+template <int MT> struct Cfg;
+template <> struct Cfg<1> { static constexpr int D = 24, NS = 6; };
+template <> struct Cfg<2> { static constexpr int D = 24, NS = 6; };
+template <> struct Cfg<4> { static constexpr int D = 24, NS = 4; };
+template <> struct Cfg<8> { static constexpr int D = 24, NS = 2; };
 
-struct LevelDesc {
-  const bf16_t* X;  // block-packed input of the level
-  int K;
-  // weight segments: up to three sites share X.  Column groups never straddle segments.
-  // pair = 1 (gate, up): group g holds tiles 2g, 2g+1 of W[0] and of W[1] and emits silu(gate)*up.
-  int n_seg, pair, norm, groups;
+struct Stage {
+  const bf16_t* X;  // input rows: row-major bf16 [M][ldx], or operand blocks (x_packed, see packed_x_offset)
+  int ldx, K, x_packed;
+  int n_seg, pair, norm;
+  int sync_before;  // the input is produced by earlier stages of this launch: wait for the grid barrier
+  int lora_shrink;  // this stage starts the shrinks of its sites (first stage of a level)
   const bf16_t* W[3];
-  int N[3], site[3], grp_end[3];
-  int* lora_cnt;  // [n_seg][M], zero at launch
-  int* k_cnt;     // [groups], zero at launch
-  // epilogue
+  int N[3], site[3];
+  int unit0, units;  // this stage covers units [unit0, unit0 + units) of the level (tiles, or gate/up tile pairs),
+  int cap;           // workgroup g taking units [g * cap, (g + 1) * cap) of them
   const bf16_t* bias[3];
   const bf16_t* resid_bf16;
   const float* resid_f32;
   int ld_resid;
   float* out_f32;
   int ld_f32;
-  bf16_t* out_rm[3];
-  int ld_rm, col_off[3];
-  bf16_t* out_pk[3];
+  bf16_t* out[3];  // row-major outputs per site
+  int ld_out[3];
+  bf16_t* out_pk;  // output as operand blocks for a later stage of this launch (one-site and gate/up stages)
 };
 
-struct DecodeParams {
-  int n_levels, M, Breq;
+struct Params {
+  int n_stages, M, Breq;
   AdapterView ad;
   const int32_t* tenant_id;
   const uint8_t* route;
   const int32_t* row_to_req;
-  int lora;        // 0: no LoRA term at all
-  float* tpart;    // [3][M][NCmax][r_max] shrink partials
-  float* tfin;     // [3][M][r_max] summed t
-  float* kpart;    // [G][2][record] segment partials
-  int* bar;        // grid barrier word, zero at launch
-  int* status;     // set to 1 when a bounded wait ran out
-  LevelDesc lv[kMaxLevels];
+  int lora;
+  float* tpart;   // [M][NCmax][r_max] shrink partials
+  float* tfin;    // [M][r_max] summed t
+  int* lora_cnt;  // [M] partials delivered; returns to zero
+  int* ready;     // [M] epoch of the launch whose t is complete
+  int nc_max;
+  int* flags;     // [kMaxGrid] grid barrier flags, monotone
+  int* status;    // set to 1 when a bounded wait ran out
+  Stage st[kMaxStages];
 };
 
-// Agent-scope (device-coherent) accesses for data that crosses workgroups.
+struct Ctrl {
+  unsigned long long tb_ptr[kMaxStages][8];
+  int tb_seg[kMaxStages][8];
+  int tb_tile[kMaxStages][8];
+  int ns[kMaxStages];
+  int x_ready;
+  int x_done[8];
+  int epoch;
+  int l_cnt;
+  int s_flag;
+  float ss_part[kSW][kMaxRows];
+  float inv_rows[kMaxRows];
+  int l_m[kMaxRows], l_r[kMaxRows], l_t[kMaxRows], l_s[kMaxRows];
+};
+static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
+
+// ---- memory-model helpers ---------------------------------------------------------------------------
+__device__ __forceinline__ int ld_agent(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(int* p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void st_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float ld_agent(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// 16-byte stores of data another workgroup reads inside this launch: written through to the memory all XCDs
+// share (a plain store may stay in the writer's L2 until the launch ends).
+__device__ __forceinline__ void st_through(u32x4* p, u32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
 }
-__device__ __forceinline__ int ld_agent(const int* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void st_through(f32x4* p, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
 }
-// All of this thread's stores have completed when this returns (then barrier, then signal).
-__device__ __forceinline__ void wait_own_stores() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): every store of this wave has been acknowledged
+// LDS flags between the waves of a workgroup.  LDS operations of a wave execute in order, so a flag
+// written after data is seen after the data; the compiler is kept from moving accesses across.
+__device__ __forceinline__ int ld_lds(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
+__device__ __forceinline__ void st_lds(int* p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+__device__ __forceinline__ void wait_lds() {
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only: vmcnt and expcnt fields left at their maxima
+}
+// vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt and lgkmcnt left at their maxima).
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+// LDS flag accesses the compiler does not see as LDS accesses: the loader's asynchronous global->LDS copies
+// would otherwise be waited for before every poll.
+__device__ __forceinline__ uint32_t lds_off(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+__device__ __forceinline__ int lds_peek(uint32_t off) {
+  int v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(off) : "memory");
+  return v;
+}
+__device__ __forceinline__ void lds_poke(uint32_t off, int v) {
+  asm volatile("ds_write_b32 %0, %1" : : "v"(off), "v"(v) : "memory");
+}
+// Every memory operation of this wave has completed (stores acknowledged by L2).
+__device__ __forceinline__ void wait_all_mem() { __builtin_amdgcn_s_waitcnt(0); }
 
-// Poll an agent-scope counter until it reaches `target`; false when the bound ran out.
-__device__ __forceinline__ bool wait_counter(const int* cnt, int target) {
-  int spins = 0;
-  while (ld_agent(cnt) < target) {
-    if (++spins >= kSpinLimit) return false;
-    __builtin_amdgcn_s_sleep(1);
-  }
-  return true;
+// Activations handed from one stage to the next are stored as the 1 KiB operand blocks the matrix cores take:
+// block (k / 32, m / 16), inside it lane (m % 16) + 16 * ((k % 32) / 8) holds 8 consecutive k.  Offset in elements.
+__device__ __host__ __forceinline__ size_t packed_x_offset(int m, int k, int MT) {
+  return ((((size_t)(k >> 5) * MT + (m >> 4)) * 64) + (m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
 }
 
 __device__ __forceinline__ float sumsq8(u32x4 v) {
@@ -130,501 +184,617 @@ __device__ __forceinline__ float sumsq8(u32x4 v) {
 
 __host__ __device__ __forceinline__ int shrink_chunks(int K) { return (K + kShrinkChunk - 1) / kShrinkChunk; }
 
-// ---- one LoRA shrink item: partial t of one routed row over one k chunk --------------------------
-// scratch: 4096 floats of LDS.  Uniform over the workgroup.
+
+// Wait until every workgroup has published `target`.  One wave.
+__device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, int lane) {
+  int spins = 0;
+  for (;;) {
+    bool ok = true;
+    for (int i = lane; i < G; i += 64) ok = ok && (ld_agent(flags + i) - target >= 0);
+    if (__all(ok)) break;
+    if (++spins >= kSpinLimit) return false;
+    __builtin_amdgcn_s_sleep(2);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  return true;
+}
+
+// ---- one LoRA shrink item by one wave: partial t of row m over one k chunk ---------------------------
 template <int MT>
-__device__ __forceinline__ void lora_shrink_item(const DecodeParams& p, const LevelDesc& lv, int item, int NC,
-                                                 float* scratch, int* s_flag) {
-  const int kc = item % NC;
-  const int m = (item / NC) % p.M;
-  const int slot = item / (NC * p.M);
-  const int site = lv.site[slot];
+__device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& sg, int m, int kc, int NC, int epoch,
+                                                 int lane) {
   const int req = p.row_to_req ? p.row_to_req[m] : m;
+  if (req < 0 || req >= p.Breq) return;
+  const int site = p.route[req];
+  int slot = -1;
+  for (int s = 0; s < sg.n_seg; ++s)
+    if (sg.site[s] == site) slot = s;
+  if (slot < 0) return;
   int tenant = 0;
   const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, site, &tenant);
   if (r == 0) return;
   const bf16_t* A = (const bf16_t*)p.ad.A[tenant * MILORA_NUM_SITES + site];
-  const int K = lv.K, rmax = p.ad.r_max;
+  const int K = sg.K, rmax = p.ad.r_max;
   const int k_lo = kc * kShrinkChunk;
   const int k_hi = k_lo + kShrinkChunk < K ? k_lo + kShrinkChunk : K;
-  float* row_part = p.tpart + (((size_t)slot * p.M + m) * NC) * rmax;
+  const bf16_t* const Xp = sg.X;
+  const bool xpk = sg.x_packed != 0;
+  const size_t xld = sg.ldx;
+  auto xval = [&](int k) __attribute__((always_inline)) -> float {
+    return bf16_to_f32(Xp[xpk ? packed_x_offset(m, k, MT) : (size_t)m * xld + k]);
+  };
+  float* row_part = p.tpart + ((size_t)m * p.nc_max) * rmax;
   float* out = row_part + (size_t)kc * rmax;
-  const bf16_t* X = lv.X;
-  auto xval = [&](int k) -> float { return bf16_to_f32(X[packed_act_offset(m, k, MT)]); };
-  const int tid = threadIdx.x;
-  if ((r & 7) == 0 && ((uintptr_t)A & 15) == 0) {
-    const int lpr = r >> 3, rpp = kThreads / lpr;  // lanes per row of A, rows per pass
-    const int cg = tid % lpr, kr = tid / lpr;
+  const int lpr = r >> 3;  // lanes per row of A when r is a multiple of 8
+  if ((r & 7) == 0 && (lpr & (lpr - 1)) == 0 && lpr <= 32 && ((uintptr_t)A & 15) == 0) {
+    const int kpl = 64 / lpr;  // rows of A per wave load
+    const int cg = lane & (lpr - 1), kr = lane / lpr;
     float acc[8];
 #pragma unroll
     for (int v = 0; v < 8; ++v) acc[v] = 0.f;
-    if (kr < rpp) {
-      const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + cg;
-      int k = k_lo + kr;
-      for (; k + 7 * rpp < k_hi; k += 8 * rpp) {
-        u32x4 a[8];
-        float x[8];
+    const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + cg;
+    int k = k_lo + kr;
+    for (; k + 15 * kpl < k_hi; k += 16 * kpl) {
+      u32x4 a[16];
+      float x[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          a[u] = __builtin_nontemporal_load(Ap + (size_t)(k + u * rpp) * lpr);
-          x[u] = xval(k + u * rpp);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            acc[2 * v] += x[u] * __uint_as_float(a[u][v] << 16);
-            acc[2 * v + 1] += x[u] * __uint_as_float(a[u][v] & 0xffff0000u);
-          }
+      for (int u = 0; u < 16; ++u) {
+        a[u] = __builtin_nontemporal_load(Ap + (size_t)(k + u * kpl) * lpr);
+        x[u] = xval(k + u * kpl);
       }
-      for (; k < k_hi; k += rpp) {
-        const u32x4 a = Ap[(size_t)k * lpr];
-        const float x = xval(k);
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          acc[2 * v] += x * __uint_as_float(a[v] << 16);
-          acc[2 * v + 1] += x * __uint_as_float(a[v] & 0xffff0000u);
+          acc[2 * v] += x[u] * __uint_as_float(a[u][v] << 16);
+          acc[2 * v + 1] += x[u] * __uint_as_float(a[u][v] & 0xffff0000u);
         }
+    }
+    for (; k < k_hi; k += kpl) {
+      const u32x4 a = Ap[(size_t)k * lpr];
+      const float x = xval(k);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        acc[2 * v] += x * __uint_as_float(a[v] << 16);
+        acc[2 * v + 1] += x * __uint_as_float(a[v] & 0xffff0000u);
       }
     }
+    // lanes with equal cg hold partial sums over different rows: fixed butterfly over the row bits
+    for (int off = lpr; off < 64; off <<= 1)
 #pragma unroll
-    for (int v = 0; v < 8; ++v) scratch[tid * 8 + v] = acc[v];
-    __syncthreads();
-    if (tid < r) {
-      const int g = tid >> 3, v = tid & 7;
-      float s = 0.f;
-      for (int q = 0; q < rpp; ++q) s += scratch[(q * lpr + g) * 8 + v];
-      st_agent(out + tid, s);
-    }
+      for (int v = 0; v < 8; ++v) acc[v] += __shfl_xor(acc[v], off, 64);
+    if (lane < lpr)
+#pragma unroll
+      for (int v = 0; v < 8; ++v) st_agent(out + lane * 8 + v, acc[v]);
   } else {
-    int rpad = 1;
-    while (rpad < r) rpad <<= 1;
-    const int c = tid % rpad, kr = tid / rpad, rpp = kThreads / rpad;
-    float acc = 0.f;
-    if (c < r)
-      for (int k = k_lo + kr; k < k_hi; k += rpp) acc += xval(k) * bf16_to_f32(A[(size_t)k * r + c]);
-    scratch[tid] = acc;
-    __syncthreads();
-    if (kr == 0 && c < r) {
-      float s = 0.f;
-      for (int q = 0; q < rpp; ++q) s += scratch[q * rpad + c];
-      st_agent(out + c, s);
+    for (int c = lane; c < r; c += 64) {
+      float acc = 0.f;
+      for (int k = k_lo; k < k_hi; ++k) acc += xval(k) * bf16_to_f32(A[(size_t)k * r + c]);
+      st_agent(out + c, acc);
     }
   }
   // publish the partial; whoever delivers the row's last partial sums them in chunk order
-  wait_own_stores();
-  __syncthreads();
-  int* cnt = &lv.lora_cnt[slot * p.M + m];
-  if (tid == 0) *s_flag = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  if (*s_flag != NC - 1) return;
-  float* fin = p.tfin + ((size_t)slot * p.M + m) * rmax;
-  const int blk = 4096 / r;  // chunks per round that fit the scratch
-  float tot = 0.f;
-  for (int k0 = 0; k0 < NC; k0 += blk) {
-    const int nk = NC - k0 < blk ? NC - k0 : blk;
-    __syncthreads();
-    for (int e = tid; e < nk * r; e += kThreads) {
-      const int q = e / r, c = e - q * r;
-      scratch[e] = ld_agent(row_part + (size_t)(k0 + q) * rmax + c);
-    }
-    __syncthreads();
-    if (tid < r)
-      for (int q = 0; q < nk; ++q) tot += scratch[q * r + tid];
+  wait_all_mem();
+  int old = 0;
+  if (lane == 0) old = __hip_atomic_fetch_add(&p.lora_cnt[m], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  old = __builtin_amdgcn_readfirstlane(old);
+  if (old != NC - 1) return;
+  float* fin = p.tfin + (size_t)m * rmax;
+  for (int c = lane; c < r; c += 64) {
+    float tot = 0.f;
+    for (int q = 0; q < NC; ++q) tot += ld_agent(row_part + (size_t)q * rmax + c);
+    st_agent(fin + c, tot);
   }
-  if (tid < r) st_agent(fin + tid, tot);
-  wait_own_stores();
-  __syncthreads();
-  if (tid == 0) __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // NC + 1: t is ready
+  if (lane == 0) st_agent(&p.lora_cnt[m], 0);
+  wait_all_mem();
+  if (lane == 0) st_agent(&p.ready[m], epoch);
 }
 
-// Workgroup that owns unit u when G workgroups split U units as [iU/G, (i+1)U/G).
-__device__ __forceinline__ int wg_of_unit(long u, long U, int G) { return (int)(((u + 1) * G + U - 1) / U) - 1; }
-
-template <int MT, int D>
-__global__ void __launch_bounds__(kThreads) decode_persist_kernel(const DecodeParams p) {
-  constexpr int kRows = MT * 16;
-  constexpr int kTile = kNT * MT * 256;            // floats of one segment's partial tile set
-  constexpr int kRec = kTile + MT * 16;            // + the per-row sums of squares
-  constexpr int kEPT = kTile / kThreads;           // floats per thread of a partial record
-  constexpr int kGroupRows = MT <= 4 ? 16 : 8;     // routed rows expanded per round
-  __shared__ float red[kTile];
-  __shared__ float t_s[kGroupRows * MILORA_MAX_RANK];
-  __shared__ float dsum[4096];
-  __shared__ float ssq_s[kWaves * MT * 16];
-  __shared__ float inv_s[kRows];
-  __shared__ int l_m[kMaxRows], l_r[kMaxRows], l_t[kMaxRows], l_a[kMaxRows];
-  __shared__ int l_cnt, s_flag;
+template <int MT>
+__global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p) {
+  constexpr int D = Cfg<MT>::D, NSMAX = Cfg<MT>::NS;
+  constexpr int kChunkBlocks = kSW;                       // k blocks per input chunk: one per stream wave
+  constexpr int kChunkBytes = kChunkBlocks * MT * 1024;
+  constexpr int NBUF = kXRegionBytes / kChunkBytes;
+  static_assert(NBUF >= 2, "input chunks");
+  static_assert(kSW * NSMAX * MT * 1024 <= kXRegionBytes, "reduction area");
+  extern __shared__ __align__(16) unsigned char smem[];
+  Ctrl& c = *reinterpret_cast<Ctrl*>(smem);
+  unsigned char* const xreg = smem + kCtrlBytes;
+  float* const red = reinterpret_cast<float*>(xreg);
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, kept in a scalar register
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wg = blockIdx.x, G = gridDim.x;
-  auto red_idx = [&](int a, int mt, int i, int ln) { return ((a * MT + mt) * 4 + i) * 64 + ln; };
 
-  for (int L = 0; L < p.n_levels; ++L) {
-    const LevelDesc& lv = p.lv[L];
-    const int KT = lv.K >> 5;
-    const int NC = shrink_chunks(lv.K);
-
-    // ---- 1. this workgroup's LoRA shrink items -----------------------------------------------------
-    if (p.lora) {
-      const int items = lv.n_seg * p.M * NC;
-      for (int item = wg; item < items; item += G) {
-        lora_shrink_item<MT>(p, lv, item, NC, dsum, &s_flag);
-        __syncthreads();
+  // ---- this workgroup's tiles in every stage -----------------------------------------------------------
+  if (tid < kMaxStages * 8) {
+    const int L = tid >> 3, a = tid & 7;
+    if (L < p.n_stages) {
+      const Stage& s = p.st[L];
+      const int f0 = wg * s.cap < s.units ? wg * s.cap : s.units, f1 = f0 + s.cap < s.units ? f0 + s.cap : s.units;
+      const int u0 = s.unit0 + f0, u1 = s.unit0 + f1;
+      const int ns = s.pair ? 2 * (u1 - u0) : (u1 - u0);
+      int ns_pad = ns;  // the ring rounds serve the tile counts that divide NSMAX
+      while (ns_pad > 0 && NSMAX % ns_pad != 0) ++ns_pad;
+      if (a == 0) c.ns[L] = ns_pad;
+      if (a >= ns && a < ns_pad) {  // filler: streams the first tile again (valid memory), result dropped
+        c.tb_ptr[L][a] = (unsigned long long)(uintptr_t)s.W[0];
+        c.tb_seg[L][a] = -1;
+        c.tb_tile[L][a] = 0;
+      }
+      if (a < ns) {
+        int seg, tile;
+        if (s.pair) {
+          seg = a & 1;
+          tile = u0 + (a >> 1);
+        } else {
+          int u = u0 + a;
+          seg = 0;
+          while (seg + 1 < s.n_seg && u >= (s.N[seg] >> 4)) {
+            u -= s.N[seg] >> 4;
+            ++seg;
+          }
+          tile = u;
+        }
+        c.tb_ptr[L][a] = (unsigned long long)(uintptr_t)s.W[seg] + (unsigned long long)tile * (s.K >> 5) * 1024ull;
+        c.tb_seg[L][a] = seg;
+        c.tb_tile[L][a] = tile;
       }
     }
+  }
+  if (tid == 0) {
+    c.x_ready = 0;
+    c.epoch = (ld_agent(p.flags + wg) >> 4) + 1;
+  }
+  if (tid < 8) c.x_done[tid] = 0;
+  __syncthreads();
+  const int epoch = __builtin_amdgcn_readfirstlane(c.epoch);
 
-    // ---- 2. this workgroup's share of the weight blocks, one segment at a time ---------------------
-    const long U = (long)lv.groups * KT;
-    const int Gl = U < (long)G ? (int)U : G;  // workgroups that stream in this level: none of them empty-handed
-    long u0 = wg < Gl ? (U * wg) / Gl : 0;
-    const long u1 = wg < Gl ? (U * (wg + 1)) / Gl : 0;
-    while (u0 < u1) {
-      const int grp = (int)(u0 / KT);
-      const int f_lo = (int)(u0 - (long)grp * KT);
-      const int f_hi = (u1 - u0) < (long)(KT - f_lo) ? f_lo + (int)(u1 - u0) : KT;
-      u0 += f_hi - f_lo;
-      // site and tiles of the group
-      int si = 0, gl = grp;
-      if (!lv.pair) {
-        while (si + 1 < lv.n_seg && gl >= lv.grp_end[si]) ++si;
-        if (si > 0) gl -= lv.grp_end[si - 1];
-      }
-      const int tiles_seg = lv.N[si] >> 4;
-      const int t0 = lv.pair ? gl * 2 : gl * kNT;  // first tile of the group inside its site
-      const int tper = lv.pair ? 2 : kNT;
-      const int nvalid = tiles_seg - t0 < tper ? tiles_seg - t0 : tper;
-      const u32x4* wp[kNT];
+  // ---- weight ring and its producer (stream waves only) ------------------------------------------------
+  u32x4 ring[D];
+  f32x4 acc[NSMAX][MT];
+  // producer state, uniform over the wave
+  int p_stage = -1, p_a = 0, p_cur = 0, p_nch = 1, p_ns = 1, p_kt = 0, p_left = 0;
+  uint32_t p_tlo = 0, p_thi = 0;  // lane a: pointer to the first block of tile a of the producer's stage
+  unsigned long long p_last = (unsigned long long)(uintptr_t)p.st[0].W[0];
+  // A stage's reduction is cut into chunks of kSW k blocks, one per stream wave.  Every workgroup walks the
+  // chunks in its own rotation (start_of): the workgroups of an XCD all read the same input rows, and in
+  // lockstep they would all hit the same few L2 channels.
+  auto chunks_of = [&](int ns, int kt) __attribute__((always_inline)) -> int { return ns > 0 ? (kt + kSW - 1) / kSW : 0; };
+  auto rounds_of = [&](int ns, int nch) __attribute__((always_inline)) -> int { return (ns * nch + D - 1) / D; };
+  auto start_of = [&](int nch) __attribute__((always_inline)) -> int {
+    const int per_xcd = (G + 7) >> 3;
+    return nch > 0 ? (int)(((long)(wg >> 3) * nch) / per_xcd) % nch : 0;
+  };
+  auto prod_advance = [&]() __attribute__((always_inline)) {
+    int ns = 1, kt = 0, left = 0, nch = 1;
+    for (;;) {
+      ++p_stage;
+      if (p_stage >= p.n_stages) break;
+      ns = __builtin_amdgcn_readfirstlane(c.ns[p_stage]);
+      kt = p.st[p_stage].K >> 5;
+      nch = chunks_of(ns, kt);
+      left = rounds_of(ns, nch) * D;
+      if (left > 0) break;
+    }
+    // past the last stage the producer keeps re-reading the last block (ring slots are always refilled)
+    const bool live = p_stage < p.n_stages;
+    const unsigned long long tp = c.tb_ptr[live ? p_stage : 0][lane & 7];
+    p_ns = live ? ns : 1;
+    p_kt = live ? kt : 0;
+    p_left = live ? left : 0x7ffffff0;
+    p_a = 0;
+    p_nch = live ? nch : 1;
+    p_cur = live ? start_of(nch) : 0;
+    p_tlo = (uint32_t)tp;
+    p_thi = (uint32_t)(tp >> 32);
+  };
+  auto prod_next = [&]() __attribute__((always_inline)) -> const gu32x4* {
+    const int kb = w + kSW * p_cur;
+    if (kb < p_kt) {
+      const uint32_t lo = __builtin_amdgcn_readlane(p_tlo, p_a), hi = __builtin_amdgcn_readlane(p_thi, p_a);
+      p_last = (((unsigned long long)hi << 32) | lo) + ((unsigned long long)kb << 10);
+    }
+    if (++p_a == p_ns) {
+      p_a = 0;
+      if (++p_cur == p_nch) p_cur = 0;
+    }
+    return reinterpret_cast<const gu32x4*>(p_last) + lane;
+  };
+  auto prod_round_end = [&]() __attribute__((always_inline)) {
+    p_left -= D;
+    if (p_left == 0) prod_advance();
+  };
+  if (w < kSW) {
+    prod_advance();
 #pragma unroll
-      for (int a = 0; a < kNT; ++a) {
-        // pair: streams 0,1 = gate tiles t0, t0+1; streams 2,3 = up tiles t0, t0+1.  A stream past the end
-        // of the site re-reads the group's first tile (valid memory) and its result is dropped.
-        const int sw = lv.pair ? (a >> 1) : si;
-        int tl = lv.pair ? (a & 1) : a;
-        if (tl >= nvalid) tl = 0;
-        wp[a] = reinterpret_cast<const u32x4*>(lv.W[sw]) + (size_t)(t0 + tl) * KT * 64 + lane;
-      }
-      const u32x4* xp = reinterpret_cast<const u32x4*>(lv.X) + lane;
+    for (int s = 0; s < D; ++s) {
+      ring[s] = __builtin_nontemporal_load(prod_next());
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    prod_round_end();
+  }
 
-      f32x4 acc[kNT][MT];
-      float ss[MT];
+  int nseq = 0;  // input chunks handed over so far (all stages)
+
+  // ---- stage end, common to all waves: reduction over the stream waves, LoRA expand, glue, stores, hand-over ----
+  auto stage_tail = [&](const int L, const Stage& sg, const int K, const int NS) __attribute__((always_inline)) {
+    __syncthreads();
+    const int tile_floats = NS * MT * 256;
+    for (int e = tid; e < tile_floats; e += kThreads) {
+      float s = red[e];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        ss[mt] = 0.f;
+      for (int ww = 1; ww < kSW; ++ww) s += red[ww * tile_floats + e];
+      red[e] = s;
+    }
+    if (tid < MT * 16) {
+      float ssq = 0.f;
 #pragma unroll
-        for (int a = 0; a < kNT; ++a) acc[a][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      }
-      // k blocks [f_lo, f_hi) of the group; this wave takes f_lo + w, f_lo + w + 4, ...
-      const int nf = (f_hi - f_lo - w + kWaves - 1) / kWaves;
-      u32x4 wb[D][kNT], xb[D][MT];
-      auto issue = [&](int s, int i) {
-        const size_t f = (size_t)f_lo + w + (size_t)i * kWaves;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) xb[s][mt] = xp[(f * MT + mt) * 64];
-#pragma unroll
-        for (int a = 0; a < kNT; ++a) wb[s][a] = __builtin_nontemporal_load(wp[a] + f * 64);
-      };
-      auto consume = [&](int s) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const bf16x8 xv = __builtin_bit_cast(bf16x8, xb[s][mt]);
-#pragma unroll
-          for (int a = 0; a < kNT; ++a)
-            acc[a][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wb[s][a]), xv, acc[a][mt], 0, 0, 0);
-          ss[mt] += sumsq8(xb[s][mt]);
-        }
-      };
-      if (nf >= 2 * D) {
-        // Register ring of D blocks per stream.  The fill and the steady loop issue unconditionally and in
-        // program order, so the number of loads in flight is the same on every path into a consume and the
-        // wait before it covers the oldest block only.
-#pragma unroll
-        for (int s = 0; s < D; ++s) {
-          issue(s, s);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        int i0 = 0;
-        for (; i0 + 2 * D <= nf; i0 += D) {
-#pragma unroll
-          for (int s = 0; s < D; ++s) {
-            consume(s);
-            issue(s, i0 + D + s);
-            __builtin_amdgcn_sched_barrier(0);
+      for (int ww = 0; ww < kSW; ++ww) ssq += c.ss_part[ww][tid];
+      c.inv_rows[tid] = sg.norm ? rsqrtf(ssq / (float)K + 1e-5f) : 1.f;
+    }
+    if (tid == 0) c.l_cnt = 0;
+    __syncthreads();
+    auto red_idx = [&](int a, int m, int nl) __attribute__((always_inline)) { return ((a * MT + (m >> 4)) * 4 + (nl & 3)) * 64 + (m & 15) + 16 * (nl >> 2); };
+
+    // ---- LoRA expand of the rows routed to this stage's sites, added to the fp32 sums -------------------
+    if (p.lora && NS > 0) {
+      for (int m = tid; m < p.M; m += kThreads) {
+        const int req = p.row_to_req ? p.row_to_req[m] : m;
+        if (req >= 0 && req < p.Breq) {
+          const int site = p.route[req];
+          for (int s = 0; s < sg.n_seg; ++s) {
+            if (sg.site[s] != site) continue;
+            int tenant = 0;
+            const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, site, &tenant);
+            if (r == 0) continue;
+            bool mine = false;  // does the workgroup hold a tile of this site?
+            for (int a = 0; a < NS; ++a) mine = mine || c.tb_seg[L][a] == s;
+            if (!mine) continue;
+            int spins = 0;
+            bool ok = true;
+            while (ld_agent(&p.ready[m]) != epoch) {
+              if (++spins >= kSpinLimit) { ok = false; break; }
+              __builtin_amdgcn_s_sleep(2);
+            }
+            if (ok) {
+              const int idx = atomicAdd(&c.l_cnt, 1);
+              c.l_m[idx] = m; c.l_r[idx] = r; c.l_t[idx] = tenant; c.l_s[idx] = s;
+            } else {
+              *p.status = 1;
+            }
           }
         }
+      }
+      __syncthreads();
+      const int cnt = c.l_cnt;
+      if (cnt > 0) {
+        // thread = (list entry, tile, column quad)
+        const int work = cnt * NS * 4;
+        for (int e = tid; e < work; e += kThreads) {
+          const int q = e & 3, a = (e >> 2) % NS, li = (e >> 2) / NS;
+          const int s = c.l_s[li];
+          if (c.tb_seg[L][a] != s) continue;
+          const int m = c.l_m[li], r = c.l_r[li];
+          const int n = c.tb_tile[L][a] * 16 + q * 4;
+          const size_t ldb = (size_t)sg.N[s];
+          const bf16_t* Bm = (const bf16_t*)p.ad.B[c.l_t[li] * MILORA_NUM_SITES + sg.site[s]] + n;
+          const float* tv = p.tfin + (size_t)m * p.ad.r_max;
+          float d[4] = {0.f, 0.f, 0.f, 0.f};
+          if (((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0) {
+            int cc = 0;
+            for (; cc + 8 <= r; cc += 8) {
+              u32x2 bb[8];
+              float t[8];
 #pragma unroll
-        for (int s = 0; s < D; ++s) {
-          consume(s);
-          if (i0 + D + s < nf) issue(s, i0 + D + s);
-        }
+              for (int u = 0; u < 8; ++u) {
+                bb[u] = *reinterpret_cast<const u32x2*>(Bm + (size_t)(cc + u) * ldb);
+                t[u] = ld_agent(tv + cc + u);
+              }
 #pragma unroll
-        for (int s = 0; s < D; ++s)
-          if (i0 + D + s < nf) consume(s);
-      } else {
-        for (int i0 = 0; i0 < nf; i0 += D) {  // short runs: everything of a round in flight at once
+              for (int u = 0; u < 8; ++u) {
+                d[0] += t[u] * __uint_as_float(bb[u][0] << 16);
+                d[1] += t[u] * __uint_as_float(bb[u][0] & 0xffff0000u);
+                d[2] += t[u] * __uint_as_float(bb[u][1] << 16);
+                d[3] += t[u] * __uint_as_float(bb[u][1] & 0xffff0000u);
+              }
+            }
+            for (; cc < r; ++cc) {
+              const u32x2 bb = *reinterpret_cast<const u32x2*>(Bm + (size_t)cc * ldb);
+              const float t = ld_agent(tv + cc);
+              d[0] += t * __uint_as_float(bb[0] << 16);
+              d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
+              d[2] += t * __uint_as_float(bb[1] << 16);
+              d[3] += t * __uint_as_float(bb[1] & 0xffff0000u);
+            }
+          } else {
+            for (int cc = 0; cc < r; ++cc) {
+              const float t = ld_agent(tv + cc);
 #pragma unroll
-          for (int s = 0; s < D; ++s)
-            if (i0 + s < nf) issue(s, i0 + s);
+              for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)cc * ldb + z]);
+            }
+          }
 #pragma unroll
-          for (int s = 0; s < D; ++s)
-            if (i0 + s < nf) consume(s);
+          for (int z = 0; z < 4; ++z) red[red_idx(a, m, q * 4 + z)] += d[z];
         }
       }
+      __syncthreads();
+    }
 
-      // ---- the four waves' partial tiles summed in wave order through LDS -------------------------
+    // ---- glue and stores: thread = (output tile, row, half of the tile's 16 columns) ---------------------------
+    {
+      const int nout = sg.pair ? NS >> 1 : NS;
+      const int work = nout * p.M * 2;
+      for (int e = tid; e < work; e += kThreads) {
+        const int hf = e & 1, m = (e >> 1) % p.M, ao = (e >> 1) / p.M;
+        const int a = sg.pair ? 2 * ao : ao;
+        const int s = sg.pair ? 0 : c.tb_seg[L][a];
+        if (s < 0) continue;
+        const int n = c.tb_tile[L][a] * 16 + hf * 8;
+        const float inv = c.inv_rows[m];
+        float val[8];
 #pragma unroll
-      for (int ww = 0; ww < kWaves; ++ww) {
-        if (w == ww) {
+        for (int z = 0; z < 8; ++z) {
+          const float v0 = red[red_idx(a, m, hf * 8 + z)] * inv;
+          if (sg.pair) val[z] = silu(v0) * (red[red_idx(a + 1, m, hf * 8 + z)] * inv);
+          else val[z] = v0;
+        }
+        if (sg.bias[s]) {
+          const u32x4 bb = *reinterpret_cast<const u32x4*>(sg.bias[s] + n);
 #pragma unroll
-          for (int a = 0; a < kNT; ++a)
+          for (int z = 0; z < 4; ++z) {
+            val[2 * z] += __uint_as_float(bb[z] << 16);
+            val[2 * z + 1] += __uint_as_float(bb[z] & 0xffff0000u);
+          }
+        }
+        if (sg.resid_bf16) {
+          const u32x4 rr = *reinterpret_cast<const u32x4*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + n);
+#pragma unroll
+          for (int z = 0; z < 4; ++z) {
+            val[2 * z] += __uint_as_float(rr[z] << 16);
+            val[2 * z + 1] += __uint_as_float(rr[z] & 0xffff0000u);
+          }
+        }
+        if (sg.resid_f32) {
+          const f32x4* rr = reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + n);
+          const f32x4 r0 = rr[0], r1 = rr[1];
+#pragma unroll
+          for (int z = 0; z < 4; ++z) {
+            val[z] += r0[z];
+            val[4 + z] += r1[z];
+          }
+        }
+        if (sg.out_f32) {
+          f32x4* oo = reinterpret_cast<f32x4*>(sg.out_f32 + (size_t)m * sg.ld_f32 + n);
+          st_through(oo, f32x4{val[0], val[1], val[2], val[3]});
+          st_through(oo + 1, f32x4{val[4], val[5], val[6], val[7]});
+        }
+        if (sg.out[s]) {
+          u32x4 o;
+#pragma unroll
+          for (int z = 0; z < 4; ++z) o[z] = pack_bf16x2(val[2 * z], val[2 * z + 1]);
+          *reinterpret_cast<u32x4*>(sg.out[s] + (size_t)m * sg.ld_out[s] + n) = o;
+        }
+        if (sg.out_pk && (sg.pair || s == sg.n_seg - 1)) {
+          u32x4 o;
+#pragma unroll
+          for (int z = 0; z < 4; ++z) o[z] = pack_bf16x2(val[2 * z], val[2 * z + 1]);
+          st_through(reinterpret_cast<u32x4*>(sg.out_pk + packed_x_offset(m, n, MT)), o);
+        }
+      }
+    }
+    // ---- hand over to the stages that read these outputs ---------------------------------------------------
+    wait_all_mem();
+    __syncthreads();
+    if (tid == 0) {
+      st_agent(p.flags + wg, epoch * 16 + (L + 1 < p.n_stages ? L + 1 : 15));
+    }
+  };
+
+  if (w < kSW) {
+    // =================================== stream waves ===================================
+    for (int L = 0; L < p.n_stages; ++L) {
+      const Stage& sg = p.st[L];
+      const int K = sg.K, KT = K >> 5;
+      const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
+      const int NCH = chunks_of(NS, KT);  // input chunks this workgroup moves
+      const int NC = shrink_chunks(K);
+      (void)NC;
+      // =================================== stream wave ===================================
+#pragma unroll
+      for (int a = 0; a < NSMAX; ++a)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[a][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      float ss[MT];  // sums of squares of the input rows over this wave's k blocks (normalisation)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) ss[mt] = 0.f;
+      const int rounds = rounds_of(NS, NCH);
+      int cseq = nseq;  // next chunk this wave starts
+      // Ring rounds.  Slot s of a round holds tile s % NS of the wave's next k block; NS divides NSMAX and the
+      // accumulator of slot s is s % NSMAX, so one piece of code serves every NS that divides NSMAX, and
+      // accumulators that met the same tile are added up afterwards.  The last round of a stage can hold slots
+      // past the end of the reduction; there both operands are zeroed instead of branching around the matrix
+      // instruction.
+      if (rounds > 0) {
+        static_assert(D % NSMAX == 0, "ring rounds must hold whole k blocks");
+        u32x4 xb[MT];
+        const unsigned char* xbuf = xreg;
+        const bool norm = sg.norm != 0;
+        int i = 0, cur = start_of(NCH), ac = 0;  // chunks begun, chunk index in this workgroup's rotation, tile
+        uint32_t wmask = 0xffffffffu;
+        for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+          for (int s = 0; s < D; ++s) {
+            if (ac == 0) {
+              const bool cvalid = i < NCH && (w + kSW * cur) < KT;
+              if (i < NCH) {
+                // next input chunk: report the previous ones finished, wait for this one
+                compiler_fence();
+                st_lds(&c.x_done[w], cseq);
+                int spins = 0;
+                while (ld_lds(&c.x_ready) <= cseq) {
+                  if (++spins >= kSpinLimit) break;
+                  __builtin_amdgcn_s_sleep(1);
+                }
+                compiler_fence();
+                xbuf = xreg + (cseq % NBUF) * kChunkBytes;
+                ++cseq;
+              }
+              wmask = cvalid ? 0xffffffffu : 0u;
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt)
+                xb[mt] = *reinterpret_cast<const u32x4*>(xbuf + ((w * MT + mt) << 10) + lane * 16) & wmask;
+              if (norm) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) ss[mt] += sumsq8(xb[mt]);
+              }
+            }
+            // Between stage ends only kSteady loads per wave stay in flight (the rest of the ring holds blocks that
+            // have landed): deeper queues of weight loads delay the input loader's loads behind them.  In the last
+            // round of a stage the landed blocks are used up without this wait, so the ring is all in flight,
+            // next stage's weights, when the stage end stalls this wave.
+            if (r + 1 < rounds) wait_vm<kSteady - 1>();
+            const u32x4 wv = ring[s] & wmask;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                if (ww == 0) red[red_idx(a, mt, i, lane)] = acc[a][mt][i];
-                else red[red_idx(a, mt, i, lane)] += acc[a][mt][i];
-              }
+              acc[s % NSMAX][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  __builtin_bit_cast(bf16x8, wv), __builtin_bit_cast(bf16x8, xb[mt]), acc[s % NSMAX][mt], 0, 0, 0);
+            ring[s] = __builtin_nontemporal_load(prod_next());
+            if (++ac == NS) {
+              ac = 0;
+              ++i;
+              if (++cur == NCH) cur = 0;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          prod_round_end();
         }
-        __syncthreads();
+        // accumulators that met the same tile, added in a fixed order
+#pragma unroll
+        for (int q = 1; q < NSMAX; ++q)
+#pragma unroll
+          for (int t = 0; t < q; ++t)
+            if (q % NS == t)
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) acc[t][mt] += acc[q][mt];
       }
+      compiler_fence();
+      st_lds(&c.x_done[w], nseq + NCH);
+      nseq += NCH;
+      __syncthreads();  // every stream wave is done with the input chunks: their LDS becomes the reduction area
+#pragma unroll
+      for (int a = 0; a < NSMAX; ++a)
+        if (a < NS)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[(((w * NS + a) * MT + mt) * 4 + i) * 64 + lane] = acc[a][mt][i];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         float v = ss[mt];
         v += __shfl_xor(v, 16, 64);
         v += __shfl_xor(v, 32, 64);
-        if (lane < 16) ssq_s[(w * MT + mt) * 16 + lane] = v;
+        if (lane < 16) c.ss_part[w][mt * 16 + lane] = v;
       }
-      __syncthreads();
-      if (tid < kRows) {
-        float s = 0.f;
-        for (int ww = 0; ww < kWaves; ++ww) s += ssq_s[(ww * MT + (tid >> 4)) * 16 + (tid & 15)];
-        inv_s[tid] = s;  // sum of squares over this segment; turned into the scale below
-      }
-      __syncthreads();
-
-      // ---- a group split over several workgroups: the last one to arrive sums in workgroup order ----
-      const long g_first_u = (long)grp * KT;
-      const int wg_first = wg_of_unit(g_first_u, U, Gl), wg_last = wg_of_unit(g_first_u + KT - 1, U, Gl);
-      const int nparts = wg_last - wg_first + 1;
-      bool finisher = true;
-      if (nparts > 1) {
-        float* mine = p.kpart + ((size_t)wg * 2 + (f_lo > 0 ? 0 : 1)) * kRec;
-#pragma unroll
-        for (int e = 0; e < kEPT; ++e) st_agent(mine + tid + e * kThreads, red[tid + e * kThreads]);
-        if (tid < kRows) st_agent(mine + kTile + tid, inv_s[tid]);
-        wait_own_stores();
-        __syncthreads();
-        if (tid == 0) s_flag = __hip_atomic_fetch_add(&lv.k_cnt[grp], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        finisher = (s_flag == nparts - 1);
-        if (finisher) {
-          float s[kEPT];
-#pragma unroll
-          for (int e = 0; e < kEPT; ++e) s[e] = 0.f;
-          float sq = 0.f;
-          for (int i = wg_first; i <= wg_last; ++i) {
-            const long st_i = (U * i) / Gl;
-            const float* rec = p.kpart + ((size_t)i * 2 + (st_i > g_first_u ? 0 : 1)) * kRec;
-            float v[kEPT];
-#pragma unroll
-            for (int e = 0; e < kEPT; ++e) v[e] = ld_agent(rec + tid + e * kThreads);
-            const float q = tid < kRows ? ld_agent(rec + kTile + tid) : 0.f;
-#pragma unroll
-            for (int e = 0; e < kEPT; ++e) s[e] += v[e];
-            sq += q;
-          }
-#pragma unroll
-          for (int e = 0; e < kEPT; ++e) red[tid + e * kThreads] = s[e];
-          if (tid < kRows) inv_s[tid] = sq;
-        }
-        __syncthreads();
-      }
-      if (finisher) {
-        if (tid < kRows) inv_s[tid] = lv.norm ? rsqrtf(inv_s[tid] / (float)lv.K + 1e-5f) : 1.f;
-        if (tid == 0) l_cnt = 0;
-        __syncthreads();
-
-        // ---- LoRA expand of the rows routed to this group's site(s), added to the fp32 sums --------
-        // column space of `red`: stream a, column nl  <->  red[a][mt][nl & 3][(m & 15) + 16 * (nl >> 2)]
-        const int n0 = t0 * 16;  // first column of the group inside its site
-        if (p.lora) {
-          for (int m = tid; m < p.M; m += kThreads) {
-            const int req = p.row_to_req ? p.row_to_req[m] : m;
-            const int nslot = lv.pair ? 2 : 1;
-            for (int a = 0; a < nslot; ++a) {
-              int tenant = 0;
-              const int slot = lv.pair ? a : si;
-              const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, lv.site[slot], &tenant);
-              if (r) {
-                // the row's t is published by workgroups that finished their shrink items before streaming
-                if (wait_counter(&lv.lora_cnt[slot * p.M + m], NC + 1)) {
-                  const int idx = atomicAdd(&l_cnt, 1);
-                  l_m[idx] = m; l_r[idx] = r; l_t[idx] = tenant; l_a[idx] = slot;
-                } else {
-                  *p.status = 1;
-                }
-              }
-            }
-          }
-          __syncthreads();
-          const int cnt = l_cnt, rmax = p.ad.r_max;
-          const int ncol = lv.pair ? 32 : 64;  // columns a routed row touches in this group
-          for (int g0 = 0; g0 < cnt; g0 += kGroupRows) {
-            const int ng = cnt - g0 < kGroupRows ? cnt - g0 : kGroupRows;
-            for (int e = tid; e < ng * rmax; e += kThreads) {
-              const int gi = e / rmax, c = e - gi * rmax, idx = g0 + gi;
-              if (c < l_r[idx]) t_s[gi * rmax + c] = ld_agent(p.tfin + ((size_t)l_a[idx] * p.M + l_m[idx]) * rmax + c);
-            }
-            __syncthreads();
-            // wave w takes ranks c = w, w+4, ...; lane = (row of a block of four, column quad)
-            const int quad = lane & 15, rsub = lane >> 4;
-            for (int gb = 0; gb < ng; gb += 4) {
-              const int gi = gb + rsub;
-              float d[4] = {0.f, 0.f, 0.f, 0.f};
-              if (gi < ng && quad * 4 < ncol) {
-                const int idx = g0 + gi, r = l_r[idx], slot = l_a[idx];
-                const size_t ldb = (size_t)lv.N[slot];
-                const int n = n0 + quad * 4;
-                if (n < (int)ldb) {
-                  const bf16_t* Bm = (const bf16_t*)p.ad.B[l_t[idx] * MILORA_NUM_SITES + lv.site[slot]] + n;
-                  const float* tv = t_s + gi * rmax;
-                  if (((uintptr_t)Bm & 7) == 0) {
-                    int c = w;
-                    for (; c + 7 * kWaves < r; c += 8 * kWaves) {
-                      u32x2 bb[8];
-#pragma unroll
-                      for (int u = 0; u < 8; ++u) bb[u] = *reinterpret_cast<const u32x2*>(Bm + (size_t)(c + u * kWaves) * ldb);
-#pragma unroll
-                      for (int u = 0; u < 8; ++u) {
-                        const float t = tv[c + u * kWaves];
-                        d[0] += t * __uint_as_float(bb[u][0] << 16);
-                        d[1] += t * __uint_as_float(bb[u][0] & 0xffff0000u);
-                        d[2] += t * __uint_as_float(bb[u][1] << 16);
-                        d[3] += t * __uint_as_float(bb[u][1] & 0xffff0000u);
-                      }
-                    }
-                    for (; c < r; c += kWaves) {
-                      const u32x2 bb = *reinterpret_cast<const u32x2*>(Bm + (size_t)c * ldb);
-                      const float t = tv[c];
-                      d[0] += t * __uint_as_float(bb[0] << 16);
-                      d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
-                      d[2] += t * __uint_as_float(bb[1] << 16);
-                      d[3] += t * __uint_as_float(bb[1] & 0xffff0000u);
-                    }
-                  } else {
-                    for (int c = w; c < r; c += kWaves) {
-                      const float t = tv[c];
-#pragma unroll
-                      for (int q = 0; q < 4; ++q) d[q] += t * bf16_to_f32(Bm[(size_t)c * ldb + q]);
-                    }
-                  }
-                }
-              }
-              if (gi < ng) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) dsum[(w * kGroupRows + gi) * 64 + quad * 4 + q] = d[q];
-              }
-            }
-            __syncthreads();
-            // the four rank classes summed in wave order and added to the base result
-            for (int e = tid; e < ng * ncol; e += kThreads) {
-              const int gi = e / ncol, col = e - gi * ncol, idx = g0 + gi;
-              float s = 0.f;
-              for (int ww = 0; ww < kWaves; ++ww) s += dsum[(ww * kGroupRows + gi) * 64 + col];
-              const int m = l_m[idx];
-              const int a = (lv.pair ? 2 * l_a[idx] : 0) + (col >> 4), nl = col & 15;
-              red[red_idx(a, m >> 4, nl & 3, (m & 15) + 16 * (nl >> 2))] += s;
-            }
-            __syncthreads();
-          }
-        }
-
-        // ---- glue and stores: thread (row m, column pair) ---------------------------------------------
-        const int nout = lv.pair ? 32 : 64;  // output columns of the group
-        const int ppr = nout >> 1;           // column pairs per row
-        const int n_lim = lv.N[si];
-        for (int e = tid; e < p.M * ppr; e += kThreads) {
-          const int m = e / ppr, pp = e - m * ppr;
-          const int col = 2 * pp;
-          const int n = n0 + col;
-          if (n >= n_lim) continue;
-          const int mt = m >> 4;
-          const float inv = inv_s[m];
-          float val[2];
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const int a = (col + q) >> 4, nl = (col + q) & 15;
-            const int ln = (m & 15) + 16 * (nl >> 2);
-            const float v0 = red[red_idx(a, mt, nl & 3, ln)] * inv;
-            if (lv.pair) val[q] = silu(v0) * (red[red_idx(a + 2, mt, nl & 3, ln)] * inv);
-            else val[q] = v0;
-          }
-          if (lv.bias[si]) {
-            val[0] += bf16_to_f32(lv.bias[si][n]);
-            val[1] += bf16_to_f32(lv.bias[si][n + 1]);
-          }
-          if (lv.resid_bf16) {
-            const uint32_t rr = *reinterpret_cast<const uint32_t*>(lv.resid_bf16 + (size_t)m * lv.ld_resid + n);
-            val[0] += __uint_as_float(rr << 16);
-            val[1] += __uint_as_float(rr & 0xffff0000u);
-          }
-          if (lv.resid_f32) {
-            const float* rr = lv.resid_f32 + (size_t)m * lv.ld_resid + n;
-            val[0] += rr[0];
-            val[1] += rr[1];
-          }
-          if (lv.out_f32) {
-            st_agent(lv.out_f32 + (size_t)m * lv.ld_f32 + n, val[0]);
-            st_agent(lv.out_f32 + (size_t)m * lv.ld_f32 + n + 1, val[1]);
-          }
-          const uint32_t packed = pack_bf16x2(val[0], val[1]);
-          if (lv.out_rm[si]) *reinterpret_cast<uint32_t*>(lv.out_rm[si] + (size_t)m * lv.ld_rm + lv.col_off[si] + n) = packed;
-          if (lv.out_pk[si]) st_agent(reinterpret_cast<uint32_t*>(lv.out_pk[si] + packed_act_offset(m, n, MT)), packed);
-        }
-      }
-      __syncthreads();  // `red` and the lists are free for the next segment
+      stage_tail(L, sg, K, NS);
     }
-
-    // ---- 3. grid barrier: the next level reads what every workgroup of this one wrote ---------------
-    if (L + 1 < p.n_levels) {
-      wait_own_stores();
-      __syncthreads();
-      if (tid == 0) {
-        __hip_atomic_fetch_add(p.bar, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (!wait_counter(p.bar, G * (L + 1))) *p.status = 1;
+  } else if (w == kLoader) {
+    // =================================== input loader ===================================
+    for (int L = 0; L < p.n_stages; ++L) {
+      const Stage& sg = p.st[L];
+      const int K = sg.K, KT = K >> 5;
+      const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
+      const int NCH = chunks_of(NS, KT);  // input chunks this workgroup moves
+      const int NC = shrink_chunks(K);
+      (void)NC;
+      // =================================== input loader ===================================
+      if (sg.sync_before && L > 0) {
+        if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
       }
-      __syncthreads();
+      if (NS > 0) {
+        // A block is the 1 KiB operand of one k block and one 16-row tile; lane l of the consumer holds
+        // (row l % 16, k group l / 16).  The copies go from global memory straight into LDS (lane l of a wave load
+        // lands at base + 16 l) and take no registers, so many chunks can be in flight; a chunk is announced once
+        // the memory counter shows it has landed.  Packed inputs are read as they lie (1 KiB contiguous per
+        // load); row-major inputs are gathered, lane l reading 16 bytes of row l % 16.
+        constexpr int LPC = kSW * MT;  // wave loads per chunk
+        constexpr int kInFlight = 63 / LPC + 1 < NBUF ? 63 / LPC + 1 : NBUF;
+        static_assert(LPC <= 63, "chunk too large for the memory counter");
+        const unsigned char* const Xb = reinterpret_cast<const unsigned char*>(sg.X);
+        const bool xpk = sg.x_packed != 0;
+        size_t loff[MT];  // byte offset of this lane's 16 bytes for row tile mt inside k block 0
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          int row = mt * 16 + (lane & 15);
+          if (row > p.M - 1) row = p.M - 1;  // rows past the batch repeat the last one; their results are dropped
+          loff[mt] = xpk ? (size_t)mt * 1024 + lane * 16 : ((size_t)row * sg.ldx + (lane >> 4) * 8) * sizeof(bf16_t);
+        }
+        const size_t kstep = xpk ? (size_t)MT * 1024 : 64;  // bytes from one k block to the next
+        const int rot = start_of(NCH);
+        const uint32_t done_off = lds_off(&c.x_done[lane < kSW ? lane : 0]), ready_off = lds_off(&c.x_ready);
+        for (int ch = 0; ch < NCH; ++ch) {
+          const int seq = nseq + ch;
+          if (seq >= NBUF) {  // the buffer's previous chunk must have been consumed by every stream wave
+            int spins = 0;
+            while (!__all(lds_peek(done_off) >= seq - NBUF + 1)) {
+              if (++spins >= kSpinLimit) break;
+              __builtin_amdgcn_s_sleep(1);
+            }
+          }
+          int cur = ch + rot;
+          if (cur >= NCH) cur -= NCH;
+          const int kb0 = cur * kSW;
+          unsigned char* dst = xreg + (seq % NBUF) * kChunkBytes;
+          // a ragged last chunk re-reads the last k block (valid memory); the stream waves zero what lies past K
+#pragma unroll
+          for (int pos = 0; pos < kSW; ++pos) {
+            const int kb = kb0 + pos < KT ? kb0 + pos : KT - 1;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xb + (size_t)kb * kstep + loff[mt]),
+                                               (__attribute__((address_space(3))) void*)(dst + ((pos * MT + mt) << 10)), 16, 0, 0);
+          }
+          if (ch >= kInFlight - 1) {
+            wait_vm<LPC * (kInFlight - 1)>();
+            lds_poke(ready_off, seq - (kInFlight - 1) + 1);
+          }
+        }
+        wait_vm<0>();
+        lds_poke(ready_off, nseq + NCH);
+      }
+      nseq += NCH;
+      __syncthreads();  // every stream wave is done with the input chunks: their LDS becomes the reduction area
+      stage_tail(L, sg, K, NS);
+    }
+  } else {
+    // =================================== LoRA wave ===================================
+    for (int L = 0; L < p.n_stages; ++L) {
+      const Stage& sg = p.st[L];
+      const int K = sg.K, KT = K >> 5;
+      const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
+      const int NCH = chunks_of(NS, KT);  // input chunks this workgroup moves
+      const int NC = shrink_chunks(K);
+      (void)NC;
+      // =================================== LoRA wave ===================================
+      if (p.lora && sg.lora_shrink) {
+        if (sg.sync_before && L > 0) {
+          if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
+        }
+        const int items = p.M * NC;
+        // spread the items of consecutive rows over the grid, and of consecutive stages over different workgroups
+        for (int it = (wg + 97 * L) % G; it < items; it += G) lora_shrink_item<MT>(p, sg, it / NC, it % NC, NC, epoch, lane);
+      }
+      __syncthreads();  // every stream wave is done with the input chunks: their LDS becomes the reduction area
+      stage_tail(L, sg, K, NS);
     }
   }
 }
 
-// Zero the synchronisation block and re-order up to two row-major activation tensors into block-packed form.
-template <int MT>
-__global__ void __launch_bounds__(kThreads) prep_kernel(int* sync, int n_sync, const u32x4* __restrict__ src0,
-                                                        u32x4* __restrict__ dst0, int K0,
-                                                        const u32x4* __restrict__ src1, u32x4* __restrict__ dst1,
-                                                        int K1, int M) {
-  const size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (g < (size_t)n_sync) sync[g] = 0;
-  const size_t n0 = src0 ? (size_t)(K0 >> 5) * MT * 64 : 0;
-  const size_t n1 = src1 ? (size_t)(K1 >> 5) * MT * 64 : 0;
-  const u32x4* src; u32x4* dst; int K; size_t q;
-  if (g < n0) { src = src0; dst = dst0; K = K0; q = g; }
-  else if (g < n0 + n1) { src = src1; dst = dst1; K = K1; q = g - n0; }
-  else return;
-  const int ln = (int)(q & 63);
-  const size_t blk = q >> 6;
-  const int mt = (int)(blk % MT), kt = (int)(blk / MT);
-  int row = mt * 16 + (ln & 15);
-  if (row > M - 1) row = M - 1;
-  dst[q] = src[((size_t)row * K + kt * 32 + (ln >> 4) * 8) / 8];
-}
-
 // Row-major [d2][d1] -> packed blocks (see milora_wlayout): one thread per 16-byte group of 8 inputs.
-__global__ void __launch_bounds__(kThreads) pack_weight_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
-                                                               int d1, int d2) {
-  const size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x;  // index of the 8-element group in dst
+__global__ void __launch_bounds__(256) pack_weight_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int d1,
+                                                          int d2) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;  // index of the 8-element group in dst
   const size_t total = (size_t)d1 * d2 / 8;
   if (g >= total) return;
   const int KT = d1 >> 5;
@@ -636,250 +806,229 @@ __global__ void __launch_bounds__(kThreads) pack_weight_kernel(const u32x4* __re
 }
 
 int mt_for(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : (M <= 64 ? 4 : 8)); }
-size_t rec_floats(int MT) { return (size_t)kNT * MT * 256 + MT * 16; }
-int groups_of(int N) { return ((N >> 4) + kNT - 1) / kNT; }
+int ns_max_for(int MT) { return MT <= 2 ? Cfg<2>::NS : (MT == 4 ? Cfg<4>::NS : Cfg<8>::NS); }
 
-template <int MT> constexpr int ring_depth() { return MT <= 2 ? 4 : (MT == 4 ? 3 : 2); }
+constexpr int kLdsBytes = kCtrlBytes + kXRegionBytes;
 
-// Workgroups of the persistent launch: one or two per CU, all resident at once (the grid barrier and the
-// bounded waits rely on that), never more than the work can feed.
+// One workgroup per compute unit, all resident at once (the grid barrier relies on that).
 template <int MT>
-int persistent_grid() {
+int stream_grid() {
   static int cached = 0;
   if (cached) return cached;
   int dev = 0, cus = 0, occ = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_persist_kernel<MT, ring_depth<MT>()>, kThreads, 0) !=
-      hipSuccess)
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_stream_kernel<MT>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
     return 0;
-  if (occ < 1) return 0;
-  cached = cus * (occ >= 2 ? 2 : 1);
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_stream_kernel<MT>, kThreads, kLdsBytes) != hipSuccess)
+    return 0;
+  if (occ < 1 || cus < 1) return 0;
+  cached = cus > kMaxGrid ? kMaxGrid : cus;
   return cached;
 }
 
 int grid_for(int MT) {
   switch (MT) {
-    case 1: return persistent_grid<1>();
-    case 2: return persistent_grid<2>();
-    case 4: return persistent_grid<4>();
-    default: return persistent_grid<8>();
+    case 1: return stream_grid<1>();
+    case 2: return stream_grid<2>();
+    case 4: return stream_grid<4>();
+    default: return stream_grid<8>();
   }
 }
 
-int launch_persist(const DecodeParams& p, int MT, int G, hipStream_t st) {
+int launch_stream(const Params& p, int MT, int G, hipStream_t st) {
   switch (MT) {
-    case 1: hipLaunchKernelGGL((decode_persist_kernel<1, ring_depth<1>()>), dim3(G), dim3(kThreads), 0, st, p); break;
-    case 2: hipLaunchKernelGGL((decode_persist_kernel<2, ring_depth<2>()>), dim3(G), dim3(kThreads), 0, st, p); break;
-    case 4: hipLaunchKernelGGL((decode_persist_kernel<4, ring_depth<4>()>), dim3(G), dim3(kThreads), 0, st, p); break;
-    default: hipLaunchKernelGGL((decode_persist_kernel<8, ring_depth<8>()>), dim3(G), dim3(kThreads), 0, st, p); break;
+    case 1: hipLaunchKernelGGL(decode_stream_kernel<1>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
+    case 2: hipLaunchKernelGGL(decode_stream_kernel<2>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
+    case 4: hipLaunchKernelGGL(decode_stream_kernel<4>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
+    default: hipLaunchKernelGGL(decode_stream_kernel<8>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
   }
   return check_launch();
 }
 
-int launch_prep(int MT, int* sync, const bf16_t* src0, bf16_t* dst0, int K0, const bf16_t* src1, bf16_t* dst1, int K1,
-                int M, hipStream_t st) {
-  size_t n = kSync;
-  const size_t np = (src0 ? (size_t)(K0 >> 5) * MT * 64 : 0) + (src1 ? (size_t)(K1 >> 5) * MT * 64 : 0);
-  if (np > n) n = np;
-  const unsigned blocks = (unsigned)((n + kThreads - 1) / kThreads);
-#define MILORA_PREP(MTV)                                                                                       \
-  hipLaunchKernelGGL(prep_kernel<MTV>, dim3(blocks), dim3(kThreads), 0, st, sync, kSync, (const u32x4*)src0, \
-                     (u32x4*)dst0, K0, (const u32x4*)src1, (u32x4*)dst1, K1, M)
-  switch (MT) {
-    case 1: MILORA_PREP(1); break;
-    case 2: MILORA_PREP(2); break;
-    case 4: MILORA_PREP(4); break;
-    default: MILORA_PREP(8); break;
+void reset_stage(Stage& s) {
+  s.X = nullptr; s.ldx = 0; s.K = 0; s.x_packed = 0; s.out_pk = nullptr; s.n_seg = 0; s.pair = 0; s.norm = 0; s.sync_before = 0; s.lora_shrink = 0;
+  s.unit0 = 0; s.units = 0; s.cap = 1;
+  for (int i = 0; i < 3; ++i) {
+    s.W[i] = nullptr; s.N[i] = 0; s.site[i] = -1; s.bias[i] = nullptr; s.out[i] = nullptr; s.ld_out[i] = 0;
   }
-#undef MILORA_PREP
-  return check_launch();
+  s.resid_bf16 = nullptr; s.resid_f32 = nullptr; s.ld_resid = 0; s.out_f32 = nullptr; s.ld_f32 = 0;
 }
 
-void reset_level(LevelDesc& l) {
-  l.X = nullptr; l.K = 0; l.n_seg = 0; l.pair = 0; l.norm = 0; l.groups = 0;
-  for (int s = 0; s < 3; ++s) {
-    l.W[s] = nullptr; l.N[s] = 0; l.site[s] = 0; l.grp_end[s] = 0;
-    l.bias[s] = nullptr; l.out_rm[s] = nullptr; l.out_pk[s] = nullptr; l.col_off[s] = 0;
+// Cut `left` units into stages: a stage hands every workgroup the same number `cap` of units, cap * per_unit
+// being a tile count the ring rounds serve (a divisor of ns_max).  Minimises the summed caps (the time,
+// in units of one tile column per workgroup), then the number of stages.  caps[] receives the choice.
+int plan_level(int left, int G, int per_unit, int ns_max, int depth, int* caps, int* n_caps) {
+  if (left <= 0) { *n_caps = 0; return 0; }
+  int best = 1 << 30, best_n = 1 << 30;
+  if (depth >= kMaxStages) return best;
+  for (int c = 1; c * per_unit <= ns_max; ++c) {
+    if (ns_max % (c * per_unit) != 0) continue;
+    int sub[kMaxStages], n_sub = 0;
+    const long rest = (long)left - (long)c * G;
+    const int t = plan_level(rest > 0 ? (int)rest : 0, G, per_unit, ns_max, depth + 1, sub, &n_sub);
+    if (t >= (1 << 30)) continue;
+    if (c + t < best || (c + t == best && n_sub + 1 < best_n)) {
+      best = c + t;
+      best_n = n_sub + 1;
+      caps[0] = c;
+      for (int i = 0; i < n_sub; ++i) caps[1 + i] = sub[i];
+      *n_caps = best_n;
+    }
   }
-  l.lora_cnt = nullptr; l.k_cnt = nullptr;
-  l.resid_bf16 = nullptr; l.resid_f32 = nullptr; l.ld_resid = 0;
-  l.out_f32 = nullptr; l.ld_f32 = 0; l.ld_rm = 0;
+  return best;
 }
 
-// ---- workspace layout of the packed-weight decode paths -------------------------------------------
+// Append the stages of one level.  In a stage workgroup g takes units [g * cap, (g + 1) * cap) of the stage's
+// range (the last workgroup with work may get fewer, the ones after it none: they spend the stage prefetching
+// the weights of their next one).  Returns false when the launch would need more stages than it has.
+bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_max) {
+  const int per_unit = level.pair ? 2 : 1;
+  int caps[kMaxStages], n_caps = 0;
+  if (plan_level(units_total, G, per_unit, ns_max, 0, caps, &n_caps) >= (1 << 30)) return false;
+  int left = units_total, u = 0;
+  for (int i = 0; i < n_caps; ++i) {
+    if (p.n_stages >= kMaxStages) return false;
+    Stage& s = p.st[p.n_stages++];
+    s = level;
+    s.unit0 = u;
+    s.units = left < caps[i] * G ? left : caps[i] * G;
+    s.cap = caps[i];
+    s.sync_before = i == 0 ? level.sync_before : 0;
+    s.lora_shrink = i == 0 ? 1 : 0;
+    u += s.units;
+    left -= s.units;
+  }
+  return true;
+}
+
+// ---- workspace layout ------------------------------------------------------------------------------------
 struct DecodeWs {
-  int* sync;       // level counters, barrier word, status
-  float* tpart;    // [3][M][NCmax][r_max]
-  float* tfin;     // [3][M][r_max]
-  float* kpart;    // [Gmax][2][record]
+  int* flags;      // [kMaxGrid] barrier flags; zero before the first launch, then owned by the kernels
+  int* lora_cnt;   // [kMaxRows]
+  int* ready;      // [kMaxRows]
+  int* status;
+  float* tpart;    // [M][NCmax][r_max]
+  float* tfin;     // [M][r_max]
   float* h_f32;    // [M][d]
-  bf16_t* pk_x;    // packed x                      (K = d)
-  bf16_t* pk_v;    // packed a = v or attn_out      (K = d)
-  bf16_t* pk_h;    // packed h                      (K = d)
-  bf16_t* pk_m;    // packed m = silu(g) * u        (K = F)
+  bf16_t* v_pk;    // a = v as operand blocks   (K = d)
+  bf16_t* h_pk;    // h as operand blocks       (K = d)
+  bf16_t* m_pk;    // m = silu(g) * u as operand blocks (K = F)
   size_t bytes;
 };
 
-constexpr int kGridMax = 512;
-
 DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
-  const int MT = mt_for(M);
   const int big = F > d ? F : d;
   size_t off = 0;
   auto take = [&](size_t n) { size_t o = off; off += align_up(n, 256); return o; };
-  const size_t o_s = take((size_t)kSync * sizeof(int));
-  const size_t o_t = take((size_t)3 * M * shrink_chunks(big) * r_max * sizeof(float));
-  const size_t o_f = take((size_t)3 * M * r_max * sizeof(float));
-  const size_t o_k = take((size_t)kGridMax * 2 * rec_floats(MT) * sizeof(float));
+  const size_t o_fl = take((size_t)(kMaxGrid + 2 * kMaxRows + 64) * sizeof(int));
+  const size_t o_t = take((size_t)M * shrink_chunks(big) * r_max * sizeof(float));
+  const size_t o_f = take((size_t)M * r_max * sizeof(float));
   const size_t o_h = take((size_t)M * d * sizeof(float));
-  const size_t o_x = take((size_t)MT * 16 * big * sizeof(bf16_t));
-  const size_t o_v = take((size_t)MT * 16 * d * sizeof(bf16_t));
-  const size_t o_hp = take((size_t)MT * 16 * d * sizeof(bf16_t));
-  const size_t o_m = take((size_t)MT * 16 * F * sizeof(bf16_t));
+  const int rows = mt_for(M) * 16;
+  const size_t o_v = take((size_t)rows * d * sizeof(bf16_t));
+  const size_t o_hb = take((size_t)rows * d * sizeof(bf16_t));
+  const size_t o_m = take((size_t)rows * F * sizeof(bf16_t));
   char* b = (char*)base;
-  return DecodeWs{(int*)(b + o_s), (float*)(b + o_t), (float*)(b + o_f), (float*)(b + o_k), (float*)(b + o_h),
-                  (bf16_t*)(b + o_x), (bf16_t*)(b + o_v), (bf16_t*)(b + o_hp), (bf16_t*)(b + o_m), off};
+  int* fl = (int*)(b + o_fl);
+  return DecodeWs{fl, fl + kMaxGrid, fl + kMaxGrid + kMaxRows, fl + kMaxGrid + 2 * kMaxRows,
+                  (float*)(b + o_t), (float*)(b + o_f), (float*)(b + o_h), (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb),
+                  (bf16_t*)(b + o_m), off};
 }
 
-void fill_common(DecodeParams& p, const DecodeWs& ws, int M, int Breq, const AdapterView& ad, const int32_t* tenant_id,
+void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const AdapterView& ad, const int32_t* tenant_id,
                  const uint8_t* route, const int32_t* row_to_req) {
-  p.M = M; p.Breq = Breq; p.ad = ad; p.tenant_id = tenant_id; p.route = route; p.row_to_req = row_to_req;
+  p.n_stages = 0; p.M = M; p.Breq = Breq; p.ad = ad; p.tenant_id = tenant_id; p.route = route; p.row_to_req = row_to_req;
   p.lora = 1;
-  p.tpart = ws.tpart; p.tfin = ws.tfin; p.kpart = ws.kpart;
-  p.bar = ws.sync + kMaxLevels * kCntPerLevel;
-  p.status = p.bar + 1;
-  for (int L = 0; L < kMaxLevels; ++L) {
-    reset_level(p.lv[L]);
-    p.lv[L].lora_cnt = ws.sync + L * kCntPerLevel;
-    p.lv[L].k_cnt = p.lv[L].lora_cnt + 3 * kMaxRows;
-  }
+  p.tpart = ws.tpart; p.tfin = ws.tfin; p.lora_cnt = ws.lora_cnt; p.ready = ws.ready; p.nc_max = shrink_chunks(Kmax);
+  p.flags = ws.flags; p.status = ws.status;
 }
 
 }  // namespace
 
 size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max) { return carve_decode_ws(nullptr, M, d, F, r_max).bytes; }
 
-// One decode step of a layer on packed weights: a preparation launch (zero the counters, pack x and
-// attn_out) and one persistent launch over the four dependency levels.  With `marks`, an event is
-// recorded after each of the two launches (slots 0 and 1).
+
+// One decode step of a layer on packed weights: one launch over the stages q,k,v | o | gate,up | down.
 int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer_weights* wts, const AdapterView& ad,
                         const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
                         bf16_t* y, bf16_t* qkv_out, void* workspace, hipStream_t st, LaunchMarks* marks) {
   const int MT = mt_for(B);
-  auto mark = [&](int slot) {
-    if (marks && slot < marks->n) (void)hipEventRecord(marks->ev[slot], st);
-  };
-  if (3 * groups_of(d) > kMaxGroups || ((F >> 4) + 1) / 2 > kMaxGroups) return MILORA_ERANGE;
-  int G = grid_for(MT);
+  const int G = grid_for(MT);
   if (G <= 0) return hip_fail(hipGetLastError());
-  if (G > kGridMax) G = kGridMax;
+  const int nsm = ns_max_for(MT);
   DecodeWs ws = carve_decode_ws(workspace, B, d, F, ad.r_max);
   const int norm = (flags & MILORA_LAYER_RMSNORM) ? 1 : 0;
-  int rc = launch_prep(MT, ws.sync, x, ws.pk_x, d, attn_out, ws.pk_v, d, B, st);
+  Params p;
+  fill_common(p, ws, B, B, F > d ? F : d, ad, tenant_id, route, nullptr);
+  Stage l;
+  // level 0: q, k, v from x
+  reset_stage(l);
+  l.X = x; l.ldx = d; l.K = d; l.n_seg = 3; l.norm = norm;
+  for (int s = 0; s < 3; ++s) {
+    l.W[s] = (const bf16_t*)wts->W[s]; l.N[s] = d; l.site[s] = s;
+    if (qkv_out) { l.out[s] = qkv_out + (size_t)s * d; l.ld_out[s] = 3 * d; }
+  }
+  if (!attn_out) l.out_pk = ws.v_pk;  // a = v goes to the next stage as operand blocks
+  if (!push_level(p, l, 3 * (d >> 4), G, nsm)) return MILORA_ERANGE;
+  // level 1: h = x + L_o(a)
+  reset_stage(l);
+  if (attn_out) { l.X = attn_out; l.ldx = d; }
+  else { l.X = ws.v_pk; l.x_packed = 1; l.sync_before = 1; }
+  l.K = d; l.n_seg = 1;
+  l.W[0] = (const bf16_t*)wts->W[3]; l.N[0] = d; l.site[0] = 3;
+  l.resid_bf16 = x; l.ld_resid = d;
+  l.out_f32 = ws.h_f32; l.ld_f32 = d;
+  l.out_pk = ws.h_pk;
+  if (!push_level(p, l, d >> 4, G, nsm)) return MILORA_ERANGE;
+  // level 2: m = silu(L_gate(n(h))) * L_up(n(h))
+  reset_stage(l);
+  l.X = ws.h_pk; l.x_packed = 1; l.K = d; l.n_seg = 2; l.pair = 1; l.norm = norm; l.sync_before = 1;
+  for (int s = 0; s < 2; ++s) { l.W[s] = (const bf16_t*)wts->W[4 + s]; l.N[s] = F; l.site[s] = 4 + s; }
+  l.out_pk = ws.m_pk;
+  if (!push_level(p, l, F >> 4, G, nsm)) return MILORA_ERANGE;
+  // level 3: y = h + L_down(m)
+  reset_stage(l);
+  l.X = ws.m_pk; l.x_packed = 1; l.K = F; l.n_seg = 1; l.sync_before = 1;
+  l.W[0] = (const bf16_t*)wts->W[6]; l.N[0] = d; l.site[0] = 6;
+  l.resid_f32 = ws.h_f32; l.ld_resid = d;
+  l.out[0] = y; l.ld_out[0] = d;
+  if (!push_level(p, l, d >> 4, G, nsm)) return MILORA_ERANGE;
+  int rc = launch_stream(p, MT, G, st);
   if (rc) return rc;
-  mark(0);
-  DecodeParams p;
-  fill_common(p, ws, B, B, ad, tenant_id, route, nullptr);
-  p.n_levels = 4;
-  {  // level 0: q, k, v from x
-    LevelDesc& l = p.lv[0];
-    l.X = ws.pk_x; l.K = d; l.n_seg = 3; l.norm = norm;
-    for (int s = 0; s < 3; ++s) {
-      l.W[s] = (const bf16_t*)wts->W[s]; l.N[s] = d; l.site[s] = s; l.grp_end[s] = (s + 1) * groups_of(d);
-      l.out_rm[s] = qkv_out; l.col_off[s] = s * d;
-    }
-    l.groups = 3 * groups_of(d);
-    l.ld_rm = 3 * d;
-    if (!attn_out) l.out_pk[2] = ws.pk_v;
-  }
-  {  // level 1: h = x + L_o(a)
-    LevelDesc& l = p.lv[1];
-    l.X = ws.pk_v; l.K = d; l.n_seg = 1;
-    l.W[0] = (const bf16_t*)wts->W[3]; l.N[0] = d; l.site[0] = 3; l.grp_end[0] = groups_of(d);
-    l.groups = groups_of(d);
-    l.resid_bf16 = x; l.ld_resid = d;
-    l.out_f32 = ws.h_f32; l.ld_f32 = d;
-    l.out_pk[0] = ws.pk_h;
-  }
-  {  // level 2: m = silu(L_gate(n(h))) * L_up(n(h))
-    LevelDesc& l = p.lv[2];
-    l.X = ws.pk_h; l.K = d; l.n_seg = 2; l.pair = 1; l.norm = norm;
-    for (int s = 0; s < 2; ++s) { l.W[s] = (const bf16_t*)wts->W[4 + s]; l.N[s] = F; l.site[s] = 4 + s; }
-    l.groups = ((F >> 4) + 1) / 2;
-    l.out_pk[0] = ws.pk_m;
-  }
-  {  // level 3: y = h + L_down(m)
-    LevelDesc& l = p.lv[3];
-    l.X = ws.pk_m; l.K = F; l.n_seg = 1;
-    l.W[0] = (const bf16_t*)wts->W[6]; l.N[0] = d; l.site[0] = 6; l.grp_end[0] = groups_of(d);
-    l.groups = groups_of(d);
-    l.resid_f32 = ws.h_f32; l.ld_resid = d;
-    l.out_rm[0] = y; l.ld_rm = d;
-  }
-  rc = launch_persist(p, MT, G, st);
-  if (rc) return rc;
-  mark(1);
+  if (marks && marks->n > 0) (void)hipEventRecord(marks->ev[0], st);
   return MILORA_OK;
 }
 
 // ---- one routed linear of M <= 128 rows on a packed weight ------------------------------------------
-struct LinearWs {
-  int* sync;
-  float* tpart;
-  float* tfin;
-  float* kpart;
-  bf16_t* pk_x;
-  size_t bytes;
-};
-
-static LinearWs carve_linear_ws(void* base, int M, int d1, int r_max) {
-  const int MT = mt_for(M);
-  size_t off = 0;
-  auto take = [&](size_t n) { size_t o = off; off += align_up(n, 256); return o; };
-  const size_t o_s = take((size_t)kSync * sizeof(int));
-  const size_t o_t = take((size_t)M * shrink_chunks(d1) * r_max * sizeof(float));
-  const size_t o_f = take((size_t)M * r_max * sizeof(float));
-  const size_t o_k = take((size_t)kGridMax * 2 * rec_floats(MT) * sizeof(float));
-  const size_t o_x = take((size_t)MT * 16 * d1 * sizeof(bf16_t));
-  char* b = (char*)base;
-  return LinearWs{(int*)(b + o_s), (float*)(b + o_t), (float*)(b + o_f), (float*)(b + o_k), (bf16_t*)(b + o_x), off};
-}
-
 size_t routed_linear_packed_workspace_bytes(int M, int d1, int d2, int r_max) {
   (void)d2;
-  return carve_linear_ws(nullptr, M, d1, r_max).bytes;
+  return carve_decode_ws(nullptr, M, 32, d1, r_max).bytes;
 }
 
 int routed_linear_packed(const bf16_t* X, int M, int d1, int d2, const int32_t* row_to_req, const bf16_t* W,
                          const bf16_t* bias, const AdapterView& ad, int site, const int32_t* tenant_id,
                          const uint8_t* route, int B, bf16_t* Y, void* workspace, hipStream_t st) {
   const int MT = mt_for(M);
-  if (groups_of(d2) > kMaxGroups) return MILORA_ERANGE;
-  int G = grid_for(MT);
+  const int G = grid_for(MT);
   if (G <= 0) return hip_fail(hipGetLastError());
-  if (G > kGridMax) G = kGridMax;
-  LinearWs ws = carve_linear_ws(workspace, M, d1, ad.r_max);
-  int rc = launch_prep(MT, ws.sync, X, ws.pk_x, d1, nullptr, nullptr, 0, M, st);
-  if (rc) return rc;
-  DecodeWs dw{};
-  dw.sync = ws.sync; dw.tpart = ws.tpart; dw.tfin = ws.tfin; dw.kpart = ws.kpart;
-  DecodeParams p;
-  fill_common(p, dw, M, B, ad, tenant_id, route, row_to_req);
-  p.n_levels = 1;
-  LevelDesc& l = p.lv[0];
-  l.X = ws.pk_x; l.K = d1; l.n_seg = 1;
-  l.W[0] = W; l.N[0] = d2; l.site[0] = site; l.grp_end[0] = groups_of(d2);
-  l.groups = groups_of(d2);
-  l.bias[0] = bias;
-  l.out_rm[0] = Y; l.ld_rm = d2;
-  return launch_persist(p, MT, G, st);
+  DecodeWs ws = carve_decode_ws(workspace, M, 32, d1, ad.r_max);
+  Params p;
+  fill_common(p, ws, M, B, d1, ad, tenant_id, route, row_to_req);
+  Stage l;
+  reset_stage(l);
+  l.X = X; l.ldx = d1; l.K = d1; l.n_seg = 1;
+  l.W[0] = W; l.N[0] = d2; l.site[0] = site; l.bias[0] = bias;
+  l.out[0] = Y; l.ld_out[0] = d2;
+  if (!push_level(p, l, d2 >> 4, G, ns_max_for(MT))) return MILORA_ERANGE;
+  return launch_stream(p, MT, G, st);
 }
 
 int pack_weight(const void* src, void* dst, int d1, int d2, hipStream_t st) {
   const size_t groups = (size_t)d1 * d2 / 8;
-  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((groups + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                     (const u32x4*)src, (u32x4*)dst, d1, d2);
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, (const u32x4*)src,
+                     (u32x4*)dst, d1, d2);
   return check_launch();
 }
 

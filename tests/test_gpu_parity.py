@@ -260,6 +260,30 @@ def test_layer_decode_packed_long_ragged_reduction(B):
     _layer_case(wl, True, mb.W_PACKED)
 
 
+def test_layer_decode_packed_reuses_buffers_across_steps():
+    # the serving pattern: one zero-filled workspace and one set of output buffers, many launches with fresh
+    # inputs; every step is checked (a stale hand-over flag or a stale cached activation would show up here)
+    wl = small(dtype="bf16", d=1024, F=2752, T=8, B=32, ranks=(16, 32), tenants="uniform", seed=71)
+    W, ad, tab = device_layer(wl)
+    Wd = [mb.milora_pack_weight(w) for w in W]
+    tid = synth.tenant_ids(wl)
+    g = torch.Generator().manual_seed(5)
+    route = torch.randint(0, 7, (wl.B,), generator=g).to(torch.uint8)
+    Wn, adn = [np_of(w) for w in W], oracle_adapters(ad)
+    ws = torch.zeros(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, tab.r_max), dtype=torch.uint8, device=DEV)
+    y = torch.empty(wl.B, wl.d, dtype=wl.torch_dtype, device=DEV)
+    qkv = torch.empty(wl.B, 3 * wl.d, dtype=wl.torch_dtype, device=DEV)
+    tid_dev, route_dev = tid.to(DEV), route.to(DEV)
+    for step in range(6):
+        x = synth.decode_input(wl, step, DEV)
+        mb.milora_layer_decode(x, Wd, tab, tid_dev, route_dev, wl.F, w_layout=mb.W_PACKED, rmsnorm=(step % 2 == 1),
+                               y=y, qkv_out=qkv, workspace=ws)
+        y_ref, qkv_ref = oracle.layer_decode(np_of(x), Wn, adn, tid.numpy(), route.numpy(), wl.F,
+                                             flags=oracle.FLAG_RMSNORM if step % 2 == 1 else 0)
+        assert_rows_close(qkv, qkv_ref, wl.torch_dtype, f"qkv step {step}")
+        assert_rows_close(y, y_ref, wl.torch_dtype, f"y step {step}")
+
+
 def test_layer_decode_rowmajor_bf16_matches_too():
     wl = small(dtype="bf16", d=256, F=352, T=4, B=9, ranks=(8,), tenants="uniform", seed=51)
     _layer_case(wl, True, mb.W_ROWMAJOR)
