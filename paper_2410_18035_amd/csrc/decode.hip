@@ -46,14 +46,15 @@ constexpr int kShrinkChunk = 512;       // reduction rows per LoRA shrink item
 constexpr int kSteady = 8;              // weight loads per stream wave in flight between stage ends
 constexpr int kSpinLimit = 1 << 22;     // polls before a bounded wait gives up
 constexpr int kCtrlBytes = 12288;       // control block at the start of LDS
-constexpr int kXRegionBytes = 144 * 1024;  // input chunks; re-used for the stage-end reduction
+constexpr int kLdsBytes = 160 * 1024;       // all of a compute unit's LDS: one workgroup per unit
 
-// Per row-tile-count tuning: ring depth, tiles per workgroup and stage.
+// Per row-tile-count tuning: ring depth, tiles per workgroup and stage, stream waves that share a partial-tile
+// area at a stage end, bytes of LDS for LoRA expands formed ahead of the stage end.
 template <int MT> struct Cfg;
-template <> struct Cfg<1> { static constexpr int D = 24, NS = 6; };
-template <> struct Cfg<2> { static constexpr int D = 24, NS = 6; };
-template <> struct Cfg<4> { static constexpr int D = 24, NS = 4; };
-template <> struct Cfg<8> { static constexpr int D = 24, NS = 2; };
+template <> struct Cfg<1> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELTA = 8192; };
+template <> struct Cfg<2> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELTA = 8192; };
+template <> struct Cfg<4> { static constexpr int D = 24, NS = 4, CHAIN = 2, DELTA = 8192; };
+template <> struct Cfg<8> { static constexpr int D = 24, NS = 2, CHAIN = 3, DELTA = 2048; };
 
 struct Stage {
   const bf16_t* X;  // input rows: row-major bf16 [M][ldx], or operand blocks (x_packed, see packed_x_offset)
@@ -83,10 +84,8 @@ struct Params {
   const uint8_t* route;
   const int32_t* row_to_req;
   int lora;
-  float* tpart;   // [M][NCmax][r_max] shrink partials
-  float* tfin;    // [M][r_max] summed t
-  int* lora_cnt;  // [M] partials delivered; returns to zero
-  int* ready;     // [M] epoch of the launch whose t is complete
+  float* tpart;   // [M][nc_max][r_max] shrink partials t = x[chunk] . A[chunk]
+  int* pready;    // [M][nc_max] epoch of the launch that wrote the partial
   int nc_max;
   int* flags;     // [kMaxGrid] grid barrier flags, monotone
   int* status;    // set to 1 when a bounded wait ran out
@@ -100,6 +99,12 @@ struct Ctrl {
   int ns[kMaxStages];
   int x_ready;
   int x_done[8];
+  int slot_turn[8];  // per partial-tile area: stream waves that have put their tiles in, counted over all stages
+  int part_cnt;      // the same over all areas
+  int sum_cnt;       // stream waves that have summed their share of the areas into `red`, over all stages
+  int red_free;      // stages whose sums the tail waves are done with
+  int tail_go;       // stages whose sums carry the LoRA terms (the loader wave may apply the glue)
+  int tail_done;     // stages whose outputs the loader wave has stored
   int epoch;
   int l_cnt;
   int s_flag;
@@ -234,16 +239,16 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
     for (int v = 0; v < 8; ++v) acc[v] = 0.f;
     const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + cg;
     int k = k_lo + kr;
-    for (; k + 15 * kpl < k_hi; k += 16 * kpl) {
-      u32x4 a[16];
-      float x[16];
+    for (; k + 31 * kpl < k_hi; k += 32 * kpl) {  // rank 32: the whole chunk in one round trip
+      u32x4 a[32];
+      float x[32];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) {
+      for (int u = 0; u < 32; ++u) {
         a[u] = __builtin_nontemporal_load(Ap + (size_t)(k + u * kpl) * lpr);
         x[u] = xval(k + u * kpl);
       }
 #pragma unroll
-      for (int u = 0; u < 16; ++u)
+      for (int u = 0; u < 32; ++u)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           acc[2 * v] += x[u] * __uint_as_float(a[u][v] << 16);
@@ -273,35 +278,30 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
       st_agent(out + c, acc);
     }
   }
-  // publish the partial; whoever delivers the row's last partial sums them in chunk order
+  // publish the partial: readers sum a row's partials themselves, in chunk order
   wait_all_mem();
-  int old = 0;
-  if (lane == 0) old = __hip_atomic_fetch_add(&p.lora_cnt[m], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  old = __builtin_amdgcn_readfirstlane(old);
-  if (old != NC - 1) return;
-  float* fin = p.tfin + (size_t)m * rmax;
-  for (int c = lane; c < r; c += 64) {
-    float tot = 0.f;
-    for (int q = 0; q < NC; ++q) tot += ld_agent(row_part + (size_t)q * rmax + c);
-    st_agent(fin + c, tot);
-  }
-  if (lane == 0) st_agent(&p.lora_cnt[m], 0);
-  wait_all_mem();
-  if (lane == 0) st_agent(&p.ready[m], epoch);
+  if (lane == 0) st_agent(&p.pready[m * p.nc_max + kc], epoch);
 }
 
 template <int MT>
 __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p) {
-  constexpr int D = Cfg<MT>::D, NSMAX = Cfg<MT>::NS;
+  constexpr int D = Cfg<MT>::D, NSMAX = Cfg<MT>::NS, CHAIN = Cfg<MT>::CHAIN;
+  constexpr int kSlots = kSW / CHAIN;                     // partial-tile areas of the stream waves at a stage end
   constexpr int kChunkBlocks = kSW;                       // k blocks per input chunk: one per stream wave
   constexpr int kChunkBytes = kChunkBlocks * MT * 1024;
-  constexpr int NBUF = kXRegionBytes / kChunkBytes;
-  static_assert(NBUF >= 2, "input chunks");
-  static_assert(kSW * NSMAX * MT * 1024 <= kXRegionBytes, "reduction area");
+  constexpr int kTileBytes = MT * 1024;                   // fp32 sums of one 16-column tile
+  constexpr int kRedBytes = NSMAX * kTileBytes;
+  constexpr int kDeltaBytes = Cfg<MT>::DELTA;
+  constexpr int kTBytes = MT == 8 ? 2048 : 4096;                       // summed shrinks t of the rows expanded ahead of the stage end
+  constexpr int kPool0 = kCtrlBytes + kRedBytes + kDeltaBytes + kTBytes;  // input chunks grow up from here, slots lie at the top
+  static_assert(kSW % CHAIN == 0, "slots");
+  static_assert(kLdsBytes - kSlots * kRedBytes - kPool0 >= 2 * kChunkBytes, "at least two input chunks next to the largest slots");
   extern __shared__ __align__(16) unsigned char smem[];
   Ctrl& c = *reinterpret_cast<Ctrl*>(smem);
-  unsigned char* const xreg = smem + kCtrlBytes;
-  float* const red = reinterpret_cast<float*>(xreg);
+  float* const red = reinterpret_cast<float*>(smem + kCtrlBytes);
+  float* const delta = reinterpret_cast<float*>(smem + kCtrlBytes + kRedBytes);
+  float* const t_lds = reinterpret_cast<float*>(smem + kCtrlBytes + kRedBytes + kDeltaBytes);
+  unsigned char* const xreg = smem + kPool0;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -345,19 +345,20 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   }
   if (tid == 0) {
     c.x_ready = 0;
+    c.part_cnt = 0;
+    c.sum_cnt = 0;
+    c.red_free = 0;
+    c.tail_go = 0;
+    c.tail_done = 0;
     c.epoch = (ld_agent(p.flags + wg) >> 4) + 1;
   }
-  if (tid < 8) c.x_done[tid] = 0;
+  if (tid < 8) {
+    c.x_done[tid] = 0;
+    c.slot_turn[tid] = 0;
+  }
   __syncthreads();
   const int epoch = __builtin_amdgcn_readfirstlane(c.epoch);
 
-  // ---- weight ring and its producer (stream waves only) ------------------------------------------------
-  u32x4 ring[D];
-  f32x4 acc[NSMAX][MT];
-  // producer state, uniform over the wave
-  int p_stage = -1, p_a = 0, p_cur = 0, p_nch = 1, p_ns = 1, p_kt = 0, p_left = 0;
-  uint32_t p_tlo = 0, p_thi = 0;  // lane a: pointer to the first block of tile a of the producer's stage
-  unsigned long long p_last = (unsigned long long)(uintptr_t)p.st[0].W[0];
   // A stage's reduction is cut into chunks of kSW k blocks, one per stream wave.  Every workgroup walks the
   // chunks in its own rotation (start_of): the workgroups of an XCD all read the same input rows, and in
   // lockstep they would all hit the same few L2 channels.
@@ -367,46 +368,72 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     const int per_xcd = (G + 7) >> 3;
     return nch > 0 ? (int)(((long)(wg >> 3) * nch) / per_xcd) % nch : 0;
   };
-  auto prod_advance = [&]() __attribute__((always_inline)) {
-    int ns = 1, kt = 0, left = 0, nch = 1;
-    for (;;) {
-      ++p_stage;
-      if (p_stage >= p.n_stages) break;
-      ns = __builtin_amdgcn_readfirstlane(c.ns[p_stage]);
-      kt = p.st[p_stage].K >> 5;
-      nch = chunks_of(ns, kt);
-      left = rounds_of(ns, nch) * D;
-      if (left > 0) break;
+  // LDS of a stage in which the workgroup holds ns tiles: kSlots areas of ns tiles at the top, input chunk
+  // buffers below them.
+  auto slots_off = [&](int ns) __attribute__((always_inline)) -> int { return kLdsBytes - kSlots * ns * kTileBytes; };
+  auto nbuf_of = [&](int ns) __attribute__((always_inline)) -> int { return (slots_off(ns) - kPool0) / kChunkBytes; };
+  auto spin_until = [&](auto cond) __attribute__((always_inline)) {
+    int spins = 0;
+    while (!cond()) {
+      if (++spins >= kSpinLimit) break;
+      __builtin_amdgcn_s_sleep(1);
     }
-    // past the last stage the producer keeps re-reading the last block (ring slots are always refilled)
-    const bool live = p_stage < p.n_stages;
-    const unsigned long long tp = c.tb_ptr[live ? p_stage : 0][lane & 7];
-    p_ns = live ? ns : 1;
-    p_kt = live ? kt : 0;
-    p_left = live ? left : 0x7ffffff0;
-    p_a = 0;
-    p_nch = live ? nch : 1;
-    p_cur = live ? start_of(nch) : 0;
-    p_tlo = (uint32_t)tp;
-    p_thi = (uint32_t)(tp >> 32);
+    compiler_fence();
   };
-  auto prod_next = [&]() __attribute__((always_inline)) -> const gu32x4* {
-    const int kb = w + kSW * p_cur;
-    if (kb < p_kt) {
-      const uint32_t lo = __builtin_amdgcn_readlane(p_tlo, p_a), hi = __builtin_amdgcn_readlane(p_thi, p_a);
-      p_last = (((unsigned long long)hi << 32) | lo) + ((unsigned long long)kb << 10);
-    }
-    if (++p_a == p_ns) {
-      p_a = 0;
-      if (++p_cur == p_nch) p_cur = 0;
-    }
-    return reinterpret_cast<const gu32x4*>(p_last) + lane;
+  // one wave: LDS written by some lanes is read by others afterwards
+  auto wave_sync = [&]() __attribute__((always_inline)) {
+    compiler_fence();
+    wait_lds();
+    compiler_fence();
   };
-  auto prod_round_end = [&]() __attribute__((always_inline)) {
-    p_left -= D;
-    if (p_left == 0) prod_advance();
-  };
+
   if (w < kSW) {
+    // ===================================== stream waves =====================================
+    u32x4 ring[D];
+    f32x4 acc[NSMAX][MT];
+    // producer state, uniform over the wave
+    int p_stage = -1, p_a = 0, p_cur = 0, p_nch = 1, p_ns = 1, p_kt = 0, p_left = 0;
+    uint32_t p_tlo = 0, p_thi = 0;  // lane a: pointer to the first block of tile a of the producer's stage
+    unsigned long long p_last = (unsigned long long)(uintptr_t)p.st[0].W[0];
+    auto prod_advance = [&]() __attribute__((always_inline)) {
+      int ns = 1, kt = 0, left = 0, nch = 1;
+      for (;;) {
+        ++p_stage;
+        if (p_stage >= p.n_stages) break;
+        ns = __builtin_amdgcn_readfirstlane(c.ns[p_stage]);
+        kt = p.st[p_stage].K >> 5;
+        nch = chunks_of(ns, kt);
+        left = rounds_of(ns, nch) * D;
+        if (left > 0) break;
+      }
+      // past the last stage the producer keeps re-reading the last block (ring slots are always refilled)
+      const bool live = p_stage < p.n_stages;
+      const unsigned long long tp = c.tb_ptr[live ? p_stage : 0][lane & 7];
+      p_ns = live ? ns : 1;
+      p_kt = live ? kt : 0;
+      p_left = live ? left : 0x7ffffff0;
+      p_a = 0;
+      p_nch = live ? nch : 1;
+      p_cur = live ? start_of(nch) : 0;
+      p_tlo = (uint32_t)tp;
+      p_thi = (uint32_t)(tp >> 32);
+    };
+    auto prod_next = [&]() __attribute__((always_inline)) -> const gu32x4* {
+      const int kb = w + kSW * p_cur;
+      if (kb < p_kt) {
+        const uint32_t lo = __builtin_amdgcn_readlane(p_tlo, p_a), hi = __builtin_amdgcn_readlane(p_thi, p_a);
+        p_last = (((unsigned long long)hi << 32) | lo) + ((unsigned long long)kb << 10);
+      }
+      if (++p_a == p_ns) {
+        p_a = 0;
+        if (++p_cur == p_nch) p_cur = 0;
+      }
+      return reinterpret_cast<const gu32x4*>(p_last) + lane;
+    };
+    auto prod_round_end = [&]() __attribute__((always_inline)) {
+      p_left -= D;
+      if (p_left == 0) prod_advance();
+    };
     prod_advance();
 #pragma unroll
     for (int s = 0; s < D; ++s) {
@@ -414,194 +441,14 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       __builtin_amdgcn_sched_barrier(0);
     }
     prod_round_end();
-  }
 
-  int nseq = 0;  // input chunks handed over so far (all stages)
-
-  // ---- stage end, common to all waves: reduction over the stream waves, LoRA expand, glue, stores, hand-over ----
-  auto stage_tail = [&](const int L, const Stage& sg, const int K, const int NS) __attribute__((always_inline)) {
-    __syncthreads();
-    const int tile_floats = NS * MT * 256;
-    for (int e = tid; e < tile_floats; e += kThreads) {
-      float s = red[e];
-#pragma unroll
-      for (int ww = 1; ww < kSW; ++ww) s += red[ww * tile_floats + e];
-      red[e] = s;
-    }
-    if (tid < MT * 16) {
-      float ssq = 0.f;
-#pragma unroll
-      for (int ww = 0; ww < kSW; ++ww) ssq += c.ss_part[ww][tid];
-      c.inv_rows[tid] = sg.norm ? rsqrtf(ssq / (float)K + 1e-5f) : 1.f;
-    }
-    if (tid == 0) c.l_cnt = 0;
-    __syncthreads();
-    auto red_idx = [&](int a, int m, int nl) __attribute__((always_inline)) { return ((a * MT + (m >> 4)) * 4 + (nl & 3)) * 64 + (m & 15) + 16 * (nl >> 2); };
-
-    // ---- LoRA expand of the rows routed to this stage's sites, added to the fp32 sums -------------------
-    if (p.lora && NS > 0) {
-      for (int m = tid; m < p.M; m += kThreads) {
-        const int req = p.row_to_req ? p.row_to_req[m] : m;
-        if (req >= 0 && req < p.Breq) {
-          const int site = p.route[req];
-          for (int s = 0; s < sg.n_seg; ++s) {
-            if (sg.site[s] != site) continue;
-            int tenant = 0;
-            const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, site, &tenant);
-            if (r == 0) continue;
-            bool mine = false;  // does the workgroup hold a tile of this site?
-            for (int a = 0; a < NS; ++a) mine = mine || c.tb_seg[L][a] == s;
-            if (!mine) continue;
-            int spins = 0;
-            bool ok = true;
-            while (ld_agent(&p.ready[m]) != epoch) {
-              if (++spins >= kSpinLimit) { ok = false; break; }
-              __builtin_amdgcn_s_sleep(2);
-            }
-            if (ok) {
-              const int idx = atomicAdd(&c.l_cnt, 1);
-              c.l_m[idx] = m; c.l_r[idx] = r; c.l_t[idx] = tenant; c.l_s[idx] = s;
-            } else {
-              *p.status = 1;
-            }
-          }
-        }
-      }
-      __syncthreads();
-      const int cnt = c.l_cnt;
-      if (cnt > 0) {
-        // thread = (list entry, tile, column quad)
-        const int work = cnt * NS * 4;
-        for (int e = tid; e < work; e += kThreads) {
-          const int q = e & 3, a = (e >> 2) % NS, li = (e >> 2) / NS;
-          const int s = c.l_s[li];
-          if (c.tb_seg[L][a] != s) continue;
-          const int m = c.l_m[li], r = c.l_r[li];
-          const int n = c.tb_tile[L][a] * 16 + q * 4;
-          const size_t ldb = (size_t)sg.N[s];
-          const bf16_t* Bm = (const bf16_t*)p.ad.B[c.l_t[li] * MILORA_NUM_SITES + sg.site[s]] + n;
-          const float* tv = p.tfin + (size_t)m * p.ad.r_max;
-          float d[4] = {0.f, 0.f, 0.f, 0.f};
-          if (((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0) {
-            int cc = 0;
-            for (; cc + 8 <= r; cc += 8) {
-              u32x2 bb[8];
-              float t[8];
-#pragma unroll
-              for (int u = 0; u < 8; ++u) {
-                bb[u] = *reinterpret_cast<const u32x2*>(Bm + (size_t)(cc + u) * ldb);
-                t[u] = ld_agent(tv + cc + u);
-              }
-#pragma unroll
-              for (int u = 0; u < 8; ++u) {
-                d[0] += t[u] * __uint_as_float(bb[u][0] << 16);
-                d[1] += t[u] * __uint_as_float(bb[u][0] & 0xffff0000u);
-                d[2] += t[u] * __uint_as_float(bb[u][1] << 16);
-                d[3] += t[u] * __uint_as_float(bb[u][1] & 0xffff0000u);
-              }
-            }
-            for (; cc < r; ++cc) {
-              const u32x2 bb = *reinterpret_cast<const u32x2*>(Bm + (size_t)cc * ldb);
-              const float t = ld_agent(tv + cc);
-              d[0] += t * __uint_as_float(bb[0] << 16);
-              d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
-              d[2] += t * __uint_as_float(bb[1] << 16);
-              d[3] += t * __uint_as_float(bb[1] & 0xffff0000u);
-            }
-          } else {
-            for (int cc = 0; cc < r; ++cc) {
-              const float t = ld_agent(tv + cc);
-#pragma unroll
-              for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)cc * ldb + z]);
-            }
-          }
-#pragma unroll
-          for (int z = 0; z < 4; ++z) red[red_idx(a, m, q * 4 + z)] += d[z];
-        }
-      }
-      __syncthreads();
-    }
-
-    // ---- glue and stores: thread = (output tile, row, half of the tile's 16 columns) ---------------------------
-    {
-      const int nout = sg.pair ? NS >> 1 : NS;
-      const int work = nout * p.M * 2;
-      for (int e = tid; e < work; e += kThreads) {
-        const int hf = e & 1, m = (e >> 1) % p.M, ao = (e >> 1) / p.M;
-        const int a = sg.pair ? 2 * ao : ao;
-        const int s = sg.pair ? 0 : c.tb_seg[L][a];
-        if (s < 0) continue;
-        const int n = c.tb_tile[L][a] * 16 + hf * 8;
-        const float inv = c.inv_rows[m];
-        float val[8];
-#pragma unroll
-        for (int z = 0; z < 8; ++z) {
-          const float v0 = red[red_idx(a, m, hf * 8 + z)] * inv;
-          if (sg.pair) val[z] = silu(v0) * (red[red_idx(a + 1, m, hf * 8 + z)] * inv);
-          else val[z] = v0;
-        }
-        if (sg.bias[s]) {
-          const u32x4 bb = *reinterpret_cast<const u32x4*>(sg.bias[s] + n);
-#pragma unroll
-          for (int z = 0; z < 4; ++z) {
-            val[2 * z] += __uint_as_float(bb[z] << 16);
-            val[2 * z + 1] += __uint_as_float(bb[z] & 0xffff0000u);
-          }
-        }
-        if (sg.resid_bf16) {
-          const u32x4 rr = *reinterpret_cast<const u32x4*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + n);
-#pragma unroll
-          for (int z = 0; z < 4; ++z) {
-            val[2 * z] += __uint_as_float(rr[z] << 16);
-            val[2 * z + 1] += __uint_as_float(rr[z] & 0xffff0000u);
-          }
-        }
-        if (sg.resid_f32) {
-          const f32x4* rr = reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + n);
-          const f32x4 r0 = rr[0], r1 = rr[1];
-#pragma unroll
-          for (int z = 0; z < 4; ++z) {
-            val[z] += r0[z];
-            val[4 + z] += r1[z];
-          }
-        }
-        if (sg.out_f32) {
-          f32x4* oo = reinterpret_cast<f32x4*>(sg.out_f32 + (size_t)m * sg.ld_f32 + n);
-          st_through(oo, f32x4{val[0], val[1], val[2], val[3]});
-          st_through(oo + 1, f32x4{val[4], val[5], val[6], val[7]});
-        }
-        if (sg.out[s]) {
-          u32x4 o;
-#pragma unroll
-          for (int z = 0; z < 4; ++z) o[z] = pack_bf16x2(val[2 * z], val[2 * z + 1]);
-          *reinterpret_cast<u32x4*>(sg.out[s] + (size_t)m * sg.ld_out[s] + n) = o;
-        }
-        if (sg.out_pk && (sg.pair || s == sg.n_seg - 1)) {
-          u32x4 o;
-#pragma unroll
-          for (int z = 0; z < 4; ++z) o[z] = pack_bf16x2(val[2 * z], val[2 * z + 1]);
-          st_through(reinterpret_cast<u32x4*>(sg.out_pk + packed_x_offset(m, n, MT)), o);
-        }
-      }
-    }
-    // ---- hand over to the stages that read these outputs ---------------------------------------------------
-    wait_all_mem();
-    __syncthreads();
-    if (tid == 0) {
-      st_agent(p.flags + wg, epoch * 16 + (L + 1 < p.n_stages ? L + 1 : 15));
-    }
-  };
-
-  if (w < kSW) {
-    // =================================== stream waves ===================================
+    int nseq = 0;  // input chunks of the earlier stages
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
       const int K = sg.K, KT = K >> 5;
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
-      const int NCH = chunks_of(NS, KT);  // input chunks this workgroup moves
-      const int NC = shrink_chunks(K);
-      (void)NC;
-      // =================================== stream wave ===================================
+      const int NCH = chunks_of(NS, KT);
+      const int NBUF = nbuf_of(NS);
 #pragma unroll
       for (int a = 0; a < NSMAX; ++a)
 #pragma unroll
@@ -610,7 +457,6 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) ss[mt] = 0.f;
       const int rounds = rounds_of(NS, NCH);
-      int cseq = nseq;  // next chunk this wave starts
       // Ring rounds.  Slot s of a round holds tile s % NS of the wave's next k block; NS divides NSMAX and the
       // accumulator of slot s is s % NSMAX, so one piece of code serves every NS that divides NSMAX, and
       // accumulators that met the same tile are added up afterwards.  The last round of a stage can hold slots
@@ -618,9 +464,13 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       // instruction.
       if (rounds > 0) {
         static_assert(D % NSMAX == 0, "ring rounds must hold whole k blocks");
-        u32x4 xb[MT];
-        const unsigned char* xbuf = xreg;
+        u32x4 xb[MT], xn[MT];  // operand blocks of the current k block and, when it was there in time, the next one
+        bool have_next = false;
+        int seen = 0;          // input chunks known to have landed (a cached copy of the loader's counter)
         const bool norm = sg.norm != 0;
+        // this lane's (row lane % 16, k group lane / 16) inside an input block: packed blocks hold it at slot
+        // lane, gathered row-major blocks at slot row * 4 + k group
+        const int rd_off = sg.x_packed ? lane * 16 : ((lane & 15) * 4 + (lane >> 4)) * 16;
         int i = 0, cur = start_of(NCH), ac = 0;  // chunks begun, chunk index in this workgroup's rotation, tile
         uint32_t wmask = 0xffffffffu;
         for (int r = 0; r < rounds; ++r) {
@@ -629,22 +479,33 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             if (ac == 0) {
               const bool cvalid = i < NCH && (w + kSW * cur) < KT;
               if (i < NCH) {
-                // next input chunk: report the previous ones finished, wait for this one
+                // next input chunk: report the previous ones finished, make sure this one has landed
                 compiler_fence();
-                st_lds(&c.x_done[w], cseq);
-                int spins = 0;
-                while (ld_lds(&c.x_ready) <= cseq) {
-                  if (++spins >= kSpinLimit) break;
-                  __builtin_amdgcn_s_sleep(1);
+                st_lds(&c.x_done[w], nseq + i);
+                if (!have_next) {
+                  if (seen <= nseq + i) {
+                    spin_until([&]() { return (seen = ld_lds(&c.x_ready)) > nseq + i; });
+                  }
+                  const unsigned char* xbuf = xreg + (i % NBUF) * kChunkBytes;
+#pragma unroll
+                  for (int mt = 0; mt < MT; ++mt)
+                    xb[mt] = *reinterpret_cast<const u32x4*>(xbuf + ((w * MT + mt) << 10) + rd_off);
+                } else {
+#pragma unroll
+                  for (int mt = 0; mt < MT; ++mt) xb[mt] = xn[mt];
                 }
-                compiler_fence();
-                xbuf = xreg + (cseq % NBUF) * kChunkBytes;
-                ++cseq;
+                // the chunk after it, if the loader is that far: its LDS reads overlap this k block's work
+                have_next = i + 1 < NCH && seen > nseq + i + 1;
+                if (have_next) {
+                  const unsigned char* xbuf = xreg + ((i + 1) % NBUF) * kChunkBytes;
+#pragma unroll
+                  for (int mt = 0; mt < MT; ++mt)
+                    xn[mt] = *reinterpret_cast<const u32x4*>(xbuf + ((w * MT + mt) << 10) + rd_off);
+                }
               }
               wmask = cvalid ? 0xffffffffu : 0u;
 #pragma unroll
-              for (int mt = 0; mt < MT; ++mt)
-                xb[mt] = *reinterpret_cast<const u32x4*>(xbuf + ((w * MT + mt) << 10) + lane * 16) & wmask;
+              for (int mt = 0; mt < MT; ++mt) xb[mt] &= wmask;
               if (norm) {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) ss[mt] += sumsq8(xb[mt]);
@@ -682,33 +543,203 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       compiler_fence();
       st_lds(&c.x_done[w], nseq + NCH);
       nseq += NCH;
-      __syncthreads();  // every stream wave is done with the input chunks: their LDS becomes the reduction area
+
+      // ---- stage end: the waves' partial tiles meet in LDS ------------------------------------------------
+      // Wave w puts its partial tiles into slot w / CHAIN (the first wave of a slot stores, the others add in
+      // wave order); when all have, each wave sums a sixth of the elements over the slots, in slot order, into
+      // `red`.  Then the wave goes on to the next stage; the two other waves finish this one.
+      if (NS > 0) {
+        const int slot = w / CHAIN, pos = w % CHAIN;
+        float* const sl = reinterpret_cast<float*>(smem + slots_off(NS) + slot * NS * kTileBytes);
+        // the slots may overlap the previous stage's slots or input chunks: everything of that stage is summed
+        spin_until([&]() { return ld_lds(&c.sum_cnt) >= L * kSW && ld_lds(&c.slot_turn[slot]) >= L * CHAIN + pos; });
 #pragma unroll
-      for (int a = 0; a < NSMAX; ++a)
-        if (a < NS)
+        for (int a = 0; a < NSMAX; ++a)
+          if (a < NS)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[(((w * NS + a) * MT + mt) * 4 + i) * 64 + lane] = acc[a][mt][i];
+              for (int q = 0; q < 4; ++q) {
+                float* e = sl + ((a * MT + mt) * 4 + q) * 64 + lane;
+                *e = (pos == 0 ? 0.f : *e) + acc[a][mt][q];
+              }
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        float v = ss[mt];
-        v += __shfl_xor(v, 16, 64);
-        v += __shfl_xor(v, 32, 64);
-        if (lane < 16) c.ss_part[w][mt * 16 + lane] = v;
+        for (int mt = 0; mt < MT; ++mt) {
+          float v = ss[mt];
+          v += __shfl_xor(v, 16, 64);
+          v += __shfl_xor(v, 32, 64);
+          if (lane < 16) c.ss_part[w][mt * 16 + lane] = v;
+        }
+        compiler_fence();
+        wait_lds();
+        st_lds(&c.slot_turn[slot], L * CHAIN + pos + 1);
+        if (lane == 0) __hip_atomic_fetch_add(&c.part_cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // all partial tiles are in, and the tail waves are done with the sums of the previous stage
+        spin_until([&]() { return ld_lds(&c.part_cnt) >= (L + 1) * kSW && ld_lds(&c.red_free) >= L; });
+        const int E = NS * MT * 256, e0 = (E * w) / kSW, e1 = (E * (w + 1)) / kSW;
+        const float* const s0 = reinterpret_cast<const float*>(smem + slots_off(NS));
+        for (int e = e0 + lane; e < e1; e += 64) {
+          float s = s0[e];
+#pragma unroll
+          for (int q = 1; q < kSlots; ++q) s += s0[q * E + e];
+          red[e] = s;
+        }
+        compiler_fence();
+        wait_lds();
+      } else {
+        spin_until([&]() { return ld_lds(&c.sum_cnt) >= L * kSW; });
+        if (lane == 0) __hip_atomic_fetch_add(&c.part_cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (lane == 0) __hip_atomic_fetch_add(&c.slot_turn[w / CHAIN], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
-      stage_tail(L, sg, K, NS);
+      if (lane == 0) __hip_atomic_fetch_add(&c.sum_cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
-  } else if (w == kLoader) {
-    // =================================== input loader ===================================
+    return;
+  }
+
+  // ======================== the two tail waves: input loader and LoRA wave ========================
+  // Stage end, run by these two waves while the stream waves already wait for the next stage's input: the LoRA
+  // expand (formed by the LoRA wave during the stage, in `delta`) is added to the fp32 sums, then both waves
+  // apply the layer glue to half of the outputs each and store them, and the LoRA wave raises the hand-over flag.
+  auto red_idx = [&](int a, int m, int nl) __attribute__((always_inline)) {
+    return ((a * MT + (m >> 4)) * 4 + (nl & 3)) * 64 + (m & 15) + 16 * (nl >> 2);
+  };
+  // LoRA expand of list entries [l0, l1): lane = (entry, tile, column quad); added to `red` or stored in `delta`
+  // shrink t[c] of row m: the chunk partials summed in chunk order
+  auto t_sum = [&](int m, int c, int NC) __attribute__((always_inline)) -> float {
+    const float* tp = p.tpart + ((size_t)m * p.nc_max) * p.ad.r_max + c;
+    float t = 0.f;
+    for (int k0 = 0; k0 < NC; k0 += 8) {  // eight loads in flight, added in chunk order
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = ld_agent(tp + (size_t)(k0 + u < NC ? k0 + u : NC - 1) * p.ad.r_max);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t += k0 + u < NC ? v[u] : 0.f;
+    }
+    return t;
+  };
+  auto expand = [&](const int L, const Stage& sg, const int NS, const int NC, int l0, int l1, bool to_red) __attribute__((always_inline)) {
+    const int work = (l1 - l0) * NS * 4;
+    for (int e = lane; e < work; e += 64) {
+      const int q = e & 3, a = (e >> 2) % NS, li = l0 + (e >> 2) / NS;
+      const int s = c.l_s[li];
+      float d[4] = {0.f, 0.f, 0.f, 0.f};
+      const bool mine = c.tb_seg[L][a] == s;
+      const int m = c.l_m[li];
+      if (mine) {
+        const int r = c.l_r[li];
+        const int n = c.tb_tile[L][a] * 16 + q * 4;
+        const size_t ldb = (size_t)sg.N[s];
+        const bf16_t* Bm = (const bf16_t*)p.ad.B[c.l_t[li] * MILORA_NUM_SITES + sg.site[s]] + n;
+        const float* tv = t_lds + (size_t)li * p.ad.r_max;  // entries formed ahead of the stage end have t in LDS
+        if (((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0) {
+          int cc = 0;
+          for (; cc + 16 <= r; cc += 16) {
+            u32x2 bb[16];
+            float t[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+              bb[u] = *reinterpret_cast<const u32x2*>(Bm + (size_t)(cc + u) * ldb);
+              t[u] = to_red ? t_sum(m, cc + u, NC) : tv[cc + u];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+              d[0] += t[u] * __uint_as_float(bb[u][0] << 16);
+              d[1] += t[u] * __uint_as_float(bb[u][0] & 0xffff0000u);
+              d[2] += t[u] * __uint_as_float(bb[u][1] << 16);
+              d[3] += t[u] * __uint_as_float(bb[u][1] & 0xffff0000u);
+            }
+          }
+          for (; cc < r; ++cc) {
+            const u32x2 bb = *reinterpret_cast<const u32x2*>(Bm + (size_t)cc * ldb);
+            const float t = to_red ? t_sum(m, cc, NC) : tv[cc];
+            d[0] += t * __uint_as_float(bb[0] << 16);
+            d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
+            d[2] += t * __uint_as_float(bb[1] << 16);
+            d[3] += t * __uint_as_float(bb[1] & 0xffff0000u);
+          }
+        } else {
+          for (int cc = 0; cc < r; ++cc) {
+            const float t = to_red ? t_sum(m, cc, NC) : tv[cc];
+#pragma unroll
+            for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)cc * ldb + z]);
+          }
+        }
+      }
+      if (to_red) {
+        if (mine)
+#pragma unroll
+          for (int z = 0; z < 4; ++z) red[red_idx(a, m, q * 4 + z)] += d[z];
+      } else {
+#pragma unroll
+        for (int z = 0; z < 4; ++z) delta[(((li - l0) * NS + a) * 4 + q) * 4 + z] = d[z];
+      }
+    }
+  };
+  // glue and stores of half of the outputs: lane = (output tile, row, half of the tile's 16 columns)
+  auto glue = [&](const int L, const Stage& sg, const int NS, const int half) __attribute__((always_inline)) {
+    const int nout = sg.pair ? NS >> 1 : NS;
+    const int work = nout * p.M * 2;
+    for (int e = half * 64 + lane; e < work; e += 128) {
+      const int hf = e & 1, m = (e >> 1) % p.M, ao = (e >> 1) / p.M;
+      const int a = sg.pair ? 2 * ao : ao;
+      const int s = sg.pair ? 0 : c.tb_seg[L][a];
+      if (s < 0) continue;
+      const int n = c.tb_tile[L][a] * 16 + hf * 8;
+      const float inv = c.inv_rows[m];
+      float val[8];
+#pragma unroll
+      for (int z = 0; z < 8; ++z) {
+        const float v0 = red[red_idx(a, m, hf * 8 + z)] * inv;
+        if (sg.pair) val[z] = silu(v0) * (red[red_idx(a + 1, m, hf * 8 + z)] * inv);
+        else val[z] = v0;
+      }
+      if (sg.bias[s]) {
+        const u32x4 bb = *reinterpret_cast<const u32x4*>(sg.bias[s] + n);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+          val[2 * z] += __uint_as_float(bb[z] << 16);
+          val[2 * z + 1] += __uint_as_float(bb[z] & 0xffff0000u);
+        }
+      }
+      if (sg.resid_bf16) {
+        const u32x4 rr = *reinterpret_cast<const u32x4*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + n);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+          val[2 * z] += __uint_as_float(rr[z] << 16);
+          val[2 * z + 1] += __uint_as_float(rr[z] & 0xffff0000u);
+        }
+      }
+      if (sg.resid_f32) {
+        const f32x4* rr = reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + n);
+        const f32x4 r0 = rr[0], r1 = rr[1];
+#pragma unroll
+        for (int z = 0; z < 4; ++z) {
+          val[z] += r0[z];
+          val[4 + z] += r1[z];
+        }
+      }
+      if (sg.out_f32) {
+        f32x4* oo = reinterpret_cast<f32x4*>(sg.out_f32 + (size_t)m * sg.ld_f32 + n);
+        st_through(oo, f32x4{val[0], val[1], val[2], val[3]});
+        st_through(oo + 1, f32x4{val[4], val[5], val[6], val[7]});
+      }
+      u32x4 o;
+#pragma unroll
+      for (int z = 0; z < 4; ++z) o[z] = pack_bf16x2(val[2 * z], val[2 * z + 1]);
+      if (sg.out[s]) *reinterpret_cast<u32x4*>(sg.out[s] + (size_t)m * sg.ld_out[s] + n) = o;
+      if (sg.out_pk && (sg.pair || s == sg.n_seg - 1)) st_through(reinterpret_cast<u32x4*>(sg.out_pk + packed_x_offset(m, n, MT)), o);
+    }
+  };
+
+  int nseq = 0;  // input chunks of the earlier stages
+  if (w == kLoader) {
+    // ===================================== input loader =====================================
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
       const int K = sg.K, KT = K >> 5;
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
-      const int NCH = chunks_of(NS, KT);  // input chunks this workgroup moves
-      const int NC = shrink_chunks(K);
-      (void)NC;
-      // =================================== input loader ===================================
+      const int NCH = chunks_of(NS, KT);
+      const int NBUF = nbuf_of(NS);
       if (sg.sync_before && L > 0) {
         if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
       }
@@ -717,35 +748,50 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         // (row l % 16, k group l / 16).  The copies go from global memory straight into LDS (lane l of a wave load
         // lands at base + 16 l) and take no registers, so many chunks can be in flight; a chunk is announced once
         // the memory counter shows it has landed.  Packed inputs are read as they lie (1 KiB contiguous per
-        // load); row-major inputs are gathered, lane l reading 16 bytes of row l % 16.
+        // load); row-major inputs are gathered, lane l reading the 16 bytes of (row l / 4, k group l % 4): four
+        // lanes cover 64 contiguous bytes of a row, which the memory pipeline takes in one piece, and the stream
+        // waves read such a block with the matching lane order.
         constexpr int LPC = kSW * MT;  // wave loads per chunk
-        constexpr int kInFlight = 63 / LPC + 1 < NBUF ? 63 / LPC + 1 : NBUF;
+        constexpr int kDepth = 63 / LPC + 1;
         static_assert(LPC <= 63, "chunk too large for the memory counter");
         const unsigned char* const Xb = reinterpret_cast<const unsigned char*>(sg.X);
         const bool xpk = sg.x_packed != 0;
         size_t loff[MT];  // byte offset of this lane's 16 bytes for row tile mt inside k block 0
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          int row = mt * 16 + (lane & 15);
+          int row = mt * 16 + (lane >> 2);
           if (row > p.M - 1) row = p.M - 1;  // rows past the batch repeat the last one; their results are dropped
-          loff[mt] = xpk ? (size_t)mt * 1024 + lane * 16 : ((size_t)row * sg.ldx + (lane >> 4) * 8) * sizeof(bf16_t);
+          loff[mt] = xpk ? (size_t)mt * 1024 + lane * 16 : ((size_t)row * sg.ldx + (lane & 3) * 8) * sizeof(bf16_t);
         }
         const size_t kstep = xpk ? (size_t)MT * 1024 : 64;  // bytes from one k block to the next
         const int rot = start_of(NCH);
         const uint32_t done_off = lds_off(&c.x_done[lane < kSW ? lane : 0]), ready_off = lds_off(&c.x_ready);
+        const uint32_t sum_off = lds_off(&c.sum_cnt);
+        // the chunk buffers may overlap the previous stage's slots: all of its partial tiles have been summed
+        spin_until([&]() { return lds_peek(sum_off) >= L * kSW; });
+        const int depth = kDepth < NBUF ? kDepth : NBUF;  // chunks in flight
+        int published = 0, done_seen = 0;
         for (int ch = 0; ch < NCH; ++ch) {
-          const int seq = nseq + ch;
-          if (seq >= NBUF) {  // the buffer's previous chunk must have been consumed by every stream wave
-            int spins = 0;
-            while (!__all(lds_peek(done_off) >= seq - NBUF + 1)) {
-              if (++spins >= kSpinLimit) break;
-              __builtin_amdgcn_s_sleep(1);
-            }
+          // the buffer's previous chunk (of this stage, or any chunk of an earlier stage) has been consumed by
+          // every stream wave
+          const int need = nseq + (ch >= NBUF ? ch - NBUF + 1 : 0);
+          if (done_seen < need) {  // a cached minimum over the stream waves: LDS is asked only when it does not suffice
+            spin_until([&]() {
+              int v = lds_peek(done_off);
+              v = lane < kSW ? v : 0x7fffffff;
+#pragma unroll
+              for (int off = 1; off < 8; off <<= 1) {
+                const int o = __shfl_xor(v, off, 64);
+                v = o < v ? o : v;
+              }
+              done_seen = __builtin_amdgcn_readfirstlane(v);
+              return done_seen >= need;
+            });
           }
           int cur = ch + rot;
           if (cur >= NCH) cur -= NCH;
           const int kb0 = cur * kSW;
-          unsigned char* dst = xreg + (seq % NBUF) * kChunkBytes;
+          unsigned char* dst = xreg + (ch % NBUF) * kChunkBytes;
           // a ragged last chunk re-reads the last k block (valid memory); the stream waves zero what lies past K
 #pragma unroll
           for (int pos = 0; pos < kSW; ++pos) {
@@ -755,28 +801,31 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
               __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xb + (size_t)kb * kstep + loff[mt]),
                                                (__attribute__((address_space(3))) void*)(dst + ((pos * MT + mt) << 10)), 16, 0, 0);
           }
-          if (ch >= kInFlight - 1) {
-            wait_vm<LPC * (kInFlight - 1)>();
-            lds_poke(ready_off, seq - (kInFlight - 1) + 1);
+          // with `depth` chunks in flight the oldest has landed once at most (depth - 1) chunks of loads are out
+          if (ch + 1 >= depth) {
+            if (depth == kDepth) wait_vm<LPC * (kDepth - 1)>();
+            else wait_vm<0>();
+            published = depth == kDepth ? ch + 2 - depth : ch + 1;
+            lds_poke(ready_off, nseq + published);
           }
         }
         wait_vm<0>();
         lds_poke(ready_off, nseq + NCH);
       }
       nseq += NCH;
-      __syncthreads();  // every stream wave is done with the input chunks: their LDS becomes the reduction area
-      stage_tail(L, sg, K, NS);
+      // ---- stage end: the LoRA wave has added the LoRA terms to the sums ---------------------------------------
+      spin_until([&]() { return ld_lds(&c.tail_go) >= L + 1; });
+      glue(L, sg, NS, 0);
+      wait_all_mem();
+      st_lds(&c.tail_done, L + 1);
     }
   } else {
-    // =================================== LoRA wave ===================================
+    // ===================================== LoRA wave =====================================
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
-      const int K = sg.K, KT = K >> 5;
+      const int K = sg.K;
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
-      const int NCH = chunks_of(NS, KT);  // input chunks this workgroup moves
       const int NC = shrink_chunks(K);
-      (void)NC;
-      // =================================== LoRA wave ===================================
       if (p.lora && sg.lora_shrink) {
         if (sg.sync_before && L > 0) {
           if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
@@ -785,8 +834,79 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         // spread the items of consecutive rows over the grid, and of consecutive stages over different workgroups
         for (int it = (wg + 97 * L) % G; it < items; it += G) lora_shrink_item<MT>(p, sg, it / NC, it % NC, NC, epoch, lane);
       }
-      __syncthreads();  // every stream wave is done with the input chunks: their LDS becomes the reduction area
-      stage_tail(L, sg, K, NS);
+      // ---- rows whose LoRA term lands in this workgroup's tiles; their expand is formed ahead of the stage end ----
+      int cnt = 0, npre = 0;
+      if (p.lora && NS > 0) {
+        if (lane == 0) c.l_cnt = 0;
+        wave_sync();
+        for (int m = lane; m < p.M; m += 64) {
+          const int req = p.row_to_req ? p.row_to_req[m] : m;
+          if (req >= 0 && req < p.Breq) {
+            const int site = p.route[req];
+            for (int s = 0; s < sg.n_seg; ++s) {
+              if (sg.site[s] != site) continue;
+              int tenant = 0;
+              const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, site, &tenant);
+              if (r == 0) continue;
+              bool mine = false;  // does the workgroup hold a tile of this site?
+              for (int a = 0; a < NS; ++a) mine = mine || c.tb_seg[L][a] == s;
+              if (!mine) continue;
+              const int idx = atomicAdd(&c.l_cnt, 1);
+              c.l_m[idx] = m; c.l_r[idx] = r; c.l_t[idx] = tenant; c.l_s[idx] = s;
+            }
+          }
+        }
+        wave_sync();
+        cnt = __builtin_amdgcn_readfirstlane(c.l_cnt);
+        // every shrink partial of these rows has been written: lane = (entry, chunk)
+        {
+          int spins = 0;
+          for (int e = lane; e < ((cnt * NC + 63) & ~63); e += 64) {
+            const int* f = p.pready + c.l_m[e < cnt * NC ? e / NC : 0] * p.nc_max + (e < cnt * NC ? e % NC : 0);
+            while (!__all(e >= cnt * NC || ld_agent(f) == epoch)) {
+              if (++spins >= kSpinLimit) { *p.status = 1; break; }
+              __builtin_amdgcn_s_sleep(2);
+            }
+          }
+        }
+        const int cap_d = kDeltaBytes / (NS * 64), cap_t = kTBytes / (p.ad.r_max * 4);  // entries `delta` and t_lds hold
+        npre = cnt < cap_d ? cnt : cap_d;
+        npre = npre < cap_t ? npre : cap_t;
+        for (int e = lane; e < npre * p.ad.r_max; e += 64) {
+          const int li = e / p.ad.r_max, cc = e - li * p.ad.r_max;
+          t_lds[e] = cc < c.l_r[li] ? t_sum(c.l_m[li], cc, NC) : 0.f;
+        }
+        wave_sync();
+        expand(L, sg, NS, NC, 0, npre, false);
+        wave_sync();
+      }
+      // ---- stage end: all six stream waves have summed their part of the tiles ---------------------------------
+      spin_until([&]() { return ld_lds(&c.sum_cnt) >= (L + 1) * kSW; });
+      for (int m = lane; m < MT * 16; m += 64) {
+        float ssq = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kSW; ++ww) ssq += c.ss_part[ww][m];
+        c.inv_rows[m] = sg.norm ? rsqrtf(ssq / (float)K + 1e-5f) : 1.f;
+      }
+      if (npre > 0) {
+        const int work = npre * NS * 4;
+        for (int e = lane; e < work; e += 64) {
+          const int q = e & 3, a = (e >> 2) % NS, li = (e >> 2) / NS;
+          if (c.tb_seg[L][a] != c.l_s[li]) continue;
+          const int m = c.l_m[li];
+#pragma unroll
+          for (int z = 0; z < 4; ++z) red[red_idx(a, m, q * 4 + z)] += delta[((li * NS + a) * 4 + q) * 4 + z];
+        }
+      }
+      if (cnt > npre) expand(L, sg, NS, NC, npre, cnt, true);
+      wave_sync();
+      st_lds(&c.tail_go, L + 1);
+      glue(L, sg, NS, 1);
+      wait_all_mem();
+      spin_until([&]() { return ld_lds(&c.tail_done) >= L + 1; });
+      // `red` may be overwritten; the outputs of both waves are in memory: hand over to the stages that read them
+      st_lds(&c.red_free, L + 1);
+      if (lane == 0) st_agent(p.flags + wg, epoch * 16 + (L + 1 < p.n_stages ? L + 1 : 15));
     }
   }
 }
@@ -808,7 +928,6 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const u32x4* __restric
 int mt_for(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : (M <= 64 ? 4 : 8)); }
 int ns_max_for(int MT) { return MT <= 2 ? Cfg<2>::NS : (MT == 4 ? Cfg<4>::NS : Cfg<8>::NS); }
 
-constexpr int kLdsBytes = kCtrlBytes + kXRegionBytes;
 
 // One workgroup per compute unit, all resident at once (the grid barrier relies on that).
 template <int MT>
@@ -906,11 +1025,9 @@ bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_ma
 // ---- workspace layout ------------------------------------------------------------------------------------
 struct DecodeWs {
   int* flags;      // [kMaxGrid] barrier flags; zero before the first launch, then owned by the kernels
-  int* lora_cnt;   // [kMaxRows]
-  int* ready;      // [kMaxRows]
   int* status;
+  int* pready;     // [M][NCmax] epochs of the shrink partials
   float* tpart;    // [M][NCmax][r_max]
-  float* tfin;     // [M][r_max]
   float* h_f32;    // [M][d]
   bf16_t* v_pk;    // a = v as operand blocks   (K = d)
   bf16_t* h_pk;    // h as operand blocks       (K = d)
@@ -922,9 +1039,9 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
   const int big = F > d ? F : d;
   size_t off = 0;
   auto take = [&](size_t n) { size_t o = off; off += align_up(n, 256); return o; };
-  const size_t o_fl = take((size_t)(kMaxGrid + 2 * kMaxRows + 64) * sizeof(int));
+  const size_t o_fl = take((size_t)(kMaxGrid + 64) * sizeof(int));
+  const size_t o_p = take((size_t)M * shrink_chunks(big) * sizeof(int));
   const size_t o_t = take((size_t)M * shrink_chunks(big) * r_max * sizeof(float));
-  const size_t o_f = take((size_t)M * r_max * sizeof(float));
   const size_t o_h = take((size_t)M * d * sizeof(float));
   const int rows = mt_for(M) * 16;
   const size_t o_v = take((size_t)rows * d * sizeof(bf16_t));
@@ -932,8 +1049,7 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
   const size_t o_m = take((size_t)rows * F * sizeof(bf16_t));
   char* b = (char*)base;
   int* fl = (int*)(b + o_fl);
-  return DecodeWs{fl, fl + kMaxGrid, fl + kMaxGrid + kMaxRows, fl + kMaxGrid + 2 * kMaxRows,
-                  (float*)(b + o_t), (float*)(b + o_f), (float*)(b + o_h), (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb),
+  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (float*)(b + o_t), (float*)(b + o_h), (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb),
                   (bf16_t*)(b + o_m), off};
 }
 
@@ -941,7 +1057,7 @@ void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const
                  const uint8_t* route, const int32_t* row_to_req) {
   p.n_stages = 0; p.M = M; p.Breq = Breq; p.ad = ad; p.tenant_id = tenant_id; p.route = route; p.row_to_req = row_to_req;
   p.lora = 1;
-  p.tpart = ws.tpart; p.tfin = ws.tfin; p.lora_cnt = ws.lora_cnt; p.ready = ws.ready; p.nc_max = shrink_chunks(Kmax);
+  p.tpart = ws.tpart; p.pready = ws.pready; p.nc_max = shrink_chunks(Kmax);
   p.flags = ws.flags; p.status = ws.status;
 }
 
