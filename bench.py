@@ -18,6 +18,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, vendor figure
 
 # HBM bytes per launch of the decode kernel from the FETCH_SIZE and WRITE_SIZE hardware counters, each scaled
 # by what the counter reads for a plain 1 GiB device copy (profiles/decode_layer_llama7b_b32_hbm_counters.txt).
@@ -56,6 +57,57 @@ def algorithmic_bytes(wl, routes, tenant_ids, ranks):
     return {"layer_step": base + lora + act, "base": base, "lora": lora, "act": act, "gate_up_launch": gate_up}
 
 
+def prefill_leg(torch, mb, synth, dev, reps=5):
+    """The many-row side of the path on the prefill configuration (16 prompts padded to 2048 rows, M = 32768):
+    router over the valid tokens, then the seven routed linears on all rows.  Returns the rates of both."""
+    wl = synth.CONFIGS["llama7b_prefill_b16"]
+    W = synth.base_weights(wl, 0, dev)
+    ad = synth.adapters(wl, 0, dev)
+    tab = mb.AdapterTable.from_tensors(ad.A, ad.B, ad.rank)
+    Wr = synth.router_weights(wl, 0, dev)
+    tid = synth.tenant_ids(wl).to(dev)
+    H, ss_host, sl_host = synth.prompts(wl, 0, dev)
+    ss, sl = ss_host.to(dev), sl_host.to(dev)
+    M = H.shape[0]
+    r2r = (torch.arange(M, device=dev) // wl.pad_to).to(torch.int32)
+    route = torch.empty(wl.B, dtype=torch.uint8, device=dev)
+    ws_route = torch.empty(mb.route_workspace_bytes(wl.B, wl.d, M), dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    route_ms = timed(lambda: mb.milora_route(H, ss, sl, tid, Wr, wl.pool, wl.act, route_out=route, want_logits=False,
+                                             workspace=ws_route))
+    Xm = torch.empty(M, wl.F, dtype=torch.float32, device=dev).normal_(0, 1).to(torch.bfloat16)
+    ws = torch.empty(mb.routed_linear_workspace_bytes(M, wl.F, wl.F, tab.r_max), dtype=torch.uint8, device=dev)
+    site_ms, flops = [], 0.0
+    for site in range(7):
+        d1, d2 = synth.site_dims(site, wl.d, wl.F)
+        assert mb.milora_routed_linear_kernel(M, d1, d2, torch.bfloat16) == mb.KERNEL_TILES
+        X = Xm if site == 6 else H
+        Y = torch.empty(M, d2, dtype=torch.bfloat16, device=dev)
+        site_ms.append(timed(lambda: mb.milora_routed_linear(X, W[site], tab, site, tid, route, row_to_req=r2r, d2=d2,
+                                                             out=Y, workspace=ws)))
+        flops += 2.0 * M * d1 * d2
+        del Y
+    total_ms = sum(site_ms)
+    tflops = flops / (total_ms * 1e-3) / 1e12
+    valid_bytes = int(sl_host.sum()) * wl.d * 2
+    return {"workload": wl.name, "rows": M, "prompts": wl.B, "valid_tokens": int(sl_host.sum()),
+            "routed_linear_ms_by_site": [round(v, 3) for v in site_ms], "base_flops": flops,
+            "tflops": round(tflops, 1), "frac_of_mfma_peak": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+            "route_ms": round(route_ms, 4),
+            "route_pool_gbs": round(valid_bytes / (route_ms * 1e-3) / 1e9, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +116,7 @@ def main():
     ap.add_argument("--workload", default="llama7b_layer_b32")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the many-row (prefill configuration) leg")
     ap.add_argument("--profile-reps", type=int, default=50)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy, the known-size kernel that hardware byte "
@@ -193,6 +246,19 @@ def main():
                "sample": f"router on all {wl.B} prompts ({t_route:.2f} s) + {done} of the {nsteps} decode steps "
                          f"({t_dec / done:.2f} s each), all {wl.B} requests; scaled to {nsteps} steps"}
 
+    # ---- what the GPU sustains on the two bounding resources, and the many-row leg ------------------
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    ceilings = {"hbm_read_gbs": round(mb.milora_measure_read_rate(big, reps=5), 1),
+                "mfma_bf16_tflops": round(mb.milora_measure_matrix_rate(4000, dev), 1)}
+    del big
+    roofline["frac_of_measured_read_rate"] = round(achieved / ceilings["hbm_read_gbs"], 4)
+    prefill = None
+    if not args.no_prefill:
+        del W, Wp, xs, ys
+        torch.cuda.empty_cache()
+        prefill = prefill_leg(torch, mb, synth, dev)
+        prefill["frac_of_measured_mfma_rate"] = round(prefill["tflops"] / ceilings["mfma_bf16_tflops"], 4)
+
     out = {
         "metric": "routed-LoRA decode tokens/s (batch 32, 32 tenants) + % HBM roofline",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -203,6 +269,8 @@ def main():
                    "tokens_per_step": tokens_per_step, "weights": "bf16 packed", "hip_graph": graph is not None},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "measured_ceilings": ceilings,
+        "prefill": prefill,
         "layer_step": {"us_in_timed_region": round(decode_ms_in_step * 1e3, 2),
                        "us_sum_of_launches": round(layer_ms * 1e3, 2),
                        "algorithmic_bytes": nbytes["layer_step"],

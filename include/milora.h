@@ -144,6 +144,15 @@ int milora_route(const void *H, int64_t M_tok, int d, int dtype, const int32_t *
  * d1 % 32 != 0 or d2 % 16 != 0, or with X, W, bias or Y not 16-byte aligned), EWORKSPACE, EHIP.
  */
 size_t milora_routed_linear_workspace_bytes(int64_t M, int d1, int d2, int r_max);
+/* Which kernel milora_routed_linear runs for these sizes when its pointers are 16-byte aligned (host
+ * logic only, no device work): MILORA_KERNEL_GENERIC (any shape, fp32 arithmetic), MILORA_KERNEL_STREAM
+ * (packed weights, the few-row weight-streaming kernel, M above MILORA_MAX_DECODE_BATCH in slices) or
+ * MILORA_KERNEL_TILES (row-major bf16 weights, M >= 64, d1 % 64 == 0, d2 % 16 == 0: 256 x 256 matrix-core
+ * tiles).  Negative status for arguments milora_routed_linear itself would reject. */
+#define MILORA_KERNEL_GENERIC 0
+#define MILORA_KERNEL_STREAM 1
+#define MILORA_KERNEL_TILES 2
+int milora_routed_linear_kernel(int64_t M, int d1, int d2, int dtype, int w_layout);
 int milora_routed_linear(const void *X, int64_t M, int d1, int d2, int dtype,
                          const int32_t *row_to_req, const void *W, int w_layout, const void *bias,
                          const milora_adapters *adapters, int site, const int32_t *tenant_id,
@@ -204,6 +213,22 @@ int milora_layer_decode_profile(const void *x, int B, int d, int F, int dtype,
  * elements each, must not overlap.  Errors: EINVAL, EUNSUPPORTED (d1 % 32 or d2 % 16 nonzero), EHIP.
  */
 int milora_pack_weight(const void *src_rowmajor, void *dst_packed, int d1, int d2, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Measurement helpers (not part of the method; for callers that report a kernel's rate against what the
+ * GPU sustains rather than against a data-sheet figure).  Both block until their kernels have finished.
+ *   milora_measure_matrix_rate: 2 x 32 x iters v_mfma_f32_16x16x32_bf16 per wave on independent
+ *     accumulators, four waves per compute unit, nothing else -> *tflops (host pointer).
+ *   milora_measure_read_rate: reads `bytes` (device, 16-byte aligned; use a buffer much larger than the
+ *     caches) `reps` times with 16-byte loads -> *gbs (host pointer).
+ *   workspace: device, milora_measure_workspace_bytes() bytes.
+ * Errors: EINVAL, EWORKSPACE, EHIP.
+ */
+size_t milora_measure_workspace_bytes(void);
+int milora_measure_matrix_rate(int iters, void *workspace, size_t workspace_bytes, double *tflops,
+                             void *stream);
+int milora_measure_read_rate(const void *buf, size_t bytes, int reps, void *workspace,
+                            size_t workspace_bytes, double *gbs, void *stream);
 
 #ifdef __cplusplus
 }

@@ -30,9 +30,10 @@ MAX_DECODE_BATCH = 128
 EXPORTS = (
     "milora_version", "milora_status_string", "milora_last_hip_error",
     "milora_route_workspace_bytes", "milora_route",
-    "milora_routed_linear_workspace_bytes", "milora_routed_linear",
+    "milora_routed_linear_workspace_bytes", "milora_routed_linear_kernel", "milora_routed_linear",
     "milora_layer_decode_workspace_bytes", "milora_layer_decode", "milora_layer_decode_profile",
     "milora_pack_weight",
+    "milora_measure_workspace_bytes", "milora_measure_matrix_rate", "milora_measure_read_rate",
 )
 
 
@@ -73,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.milora_route.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, sz, vp]
         L.milora_routed_linear_workspace_bytes.restype = sz
         L.milora_routed_linear_workspace_bytes.argtypes = [i64, i32, i32, i32]
+        L.milora_routed_linear_kernel.restype = i32
+        L.milora_routed_linear_kernel.argtypes = [i64, i32, i32, i32, i32]
         L.milora_routed_linear.restype = i32
         L.milora_routed_linear.argtypes = [vp, i64, i32, i32, i32, vp, vp, i32, vp, ctypes.POINTER(_Adapters), i32,
                                            vp, vp, i32, vp, vp, sz, vp]
@@ -85,6 +88,12 @@ def lib() -> ctypes.CDLL:
         L.milora_layer_decode_profile.argtypes = L.milora_layer_decode.argtypes + [i32, ctypes.POINTER(ctypes.c_float)]
         L.milora_pack_weight.restype = i32
         L.milora_pack_weight.argtypes = [vp, vp, i32, i32, vp]
+        L.milora_measure_workspace_bytes.restype = sz
+        L.milora_measure_workspace_bytes.argtypes = []
+        L.milora_measure_matrix_rate.restype = i32
+        L.milora_measure_matrix_rate.argtypes = [i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
+        L.milora_measure_read_rate.restype = i32
+        L.milora_measure_read_rate.argtypes = [vp, sz, i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
         _lib = L
     return _lib
 
@@ -197,6 +206,14 @@ def routed_linear_workspace_bytes(M: int, d1: int, d2: int, r_max: int) -> int:
     return int(lib().milora_routed_linear_workspace_bytes(M, d1, d2, r_max))
 
 
+KERNEL_GENERIC, KERNEL_STREAM, KERNEL_TILES = 0, 1, 2
+
+
+def milora_routed_linear_kernel(M: int, d1: int, d2: int, dtype: torch.dtype, w_layout: int = W_ROWMAJOR) -> int:
+    code = {torch.bfloat16: 0, torch.float32: 1}[dtype] if not isinstance(dtype, int) else dtype
+    return int(lib().milora_routed_linear_kernel(M, d1, d2, code, w_layout))
+
+
 def milora_routed_linear(X: torch.Tensor, W: torch.Tensor, adapters: AdapterTable, site: int,
                          tenant_id: torch.Tensor, route: torch.Tensor, row_to_req: Optional[torch.Tensor] = None,
                          bias: Optional[torch.Tensor] = None, w_layout: int = W_ROWMAJOR,
@@ -281,3 +298,24 @@ def milora_pack_weight(W: torch.Tensor) -> torch.Tensor:
     if rc != 0:
         raise MiloraError(rc, "milora_pack_weight")
     return out
+
+
+def milora_measure_matrix_rate(iters: int = 4000, device="cuda:0") -> float:
+    """Sustained bf16 matrix-core rate of the GPU in TFLOP/s (a kernel of nothing but matrix instructions)."""
+    ws = torch.empty(lib().milora_measure_workspace_bytes(), dtype=torch.uint8, device=device)
+    out = ctypes.c_double(0.0)
+    rc = lib().milora_measure_matrix_rate(iters, _dev(ws), ws.numel(), ctypes.byref(out), _stream())
+    if rc:
+        raise MiloraError(rc, "milora_measure_matrix_rate")
+    return out.value
+
+
+def milora_measure_read_rate(buf: torch.Tensor, reps: int = 5) -> float:
+    """Rate in GB/s at which one pass of 16-byte loads reads `buf` (make it much larger than the caches)."""
+    ws = torch.empty(lib().milora_measure_workspace_bytes(), dtype=torch.uint8, device=buf.device)
+    out = ctypes.c_double(0.0)
+    nbytes = buf.numel() * buf.element_size()
+    rc = lib().milora_measure_read_rate(_dev(buf), nbytes, reps, _dev(ws), ws.numel(), ctypes.byref(out), _stream())
+    if rc:
+        raise MiloraError(rc, "milora_measure_read_rate")
+    return out.value

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT_DIR = os.path.join(HERE, "_lib")
 LIB = os.path.join(OUT_DIR, "libmilora.so")
-SOURCES = ["api.hip", "route.hip", "linear_generic.hip", "decode.hip", "prefill.hip"]
+SOURCES = ["api.hip", "route.hip", "linear_generic.hip", "decode.hip", "prefill.hip", "measure.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

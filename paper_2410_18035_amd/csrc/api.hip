@@ -215,6 +215,18 @@ extern "C" size_t milora_routed_linear_workspace_bytes(int64_t M, int d1, int d2
   return generic > packed ? generic : packed;
 }
 
+extern "C" int milora_routed_linear_kernel(int64_t M, int d1, int d2, int dtype, int w_layout) {
+  if (M < 1 || d1 < 1 || d2 < 1 || !valid_dtype(dtype)) return MILORA_EINVAL;
+  if (w_layout != MILORA_W_ROWMAJOR && w_layout != MILORA_W_PACKED) return MILORA_EINVAL;
+  if (w_layout == MILORA_W_PACKED) {
+    if (dtype != MILORA_BF16 || !packed_shape_ok(d1, d2)) return MILORA_EUNSUPPORTED;
+    return MILORA_KERNEL_STREAM;
+  }
+  const void* aligned = (const void*)(uintptr_t)256;
+  if (dtype == MILORA_BF16 && prefill_supported(M, d1, d2, aligned, aligned, aligned)) return MILORA_KERNEL_TILES;
+  return MILORA_KERNEL_GENERIC;
+}
+
 extern "C" int milora_routed_linear(const void* X, int64_t M, int d1, int d2, int dtype, const int32_t* row_to_req,
                                     const void* W, int w_layout, const void* bias, const milora_adapters* adapters,
                                     int site, const int32_t* tenant_id, const uint8_t* route, int B, void* Y,

@@ -3,9 +3,10 @@
 //
 // One workgroup of four waves computes a 256 x 256 tile of Y with the bf16 matrix cores
 // (v_mfma_f32_16x16x32_bf16, fp32 accumulators, 128 x 128 per wave).  X and W are both contiguous along the
-// reduction index, so a 16-row x 32-k block of either is what one matrix-core operand takes; the blocks are
-// copied from global memory straight into LDS (global_load_lds_dwordx4, no registers) in that operand order,
-// four k steps deep (4 x 32 KB), and read back with one conflict-free 16-byte LDS load per lane and block.
+// reduction index: 16-row x 64-k blocks of either are copied from global memory straight into LDS
+// (global_load_lds_dwordx4, no registers; whole 128-byte lines per row), in a ring of five half steps of
+// 32 KB (three in flight while two are read), and read back as matrix-core operands with one conflict-free
+// 16-byte LDS load per lane, block and k half.
 // The LoRA term enters as extra k steps: t = X W^A (fp32, computed beforehand) split into two bf16 halves
 // (hi + lo, so nothing of t's precision is lost) against W^B of the tenant, masked to that tenant's rows.
 // Bias is added and the result rounded once at the store.
@@ -19,13 +20,13 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTM = 256, kTN = 256, kTK = 32;
-constexpr int kStages = 4;
+constexpr int kTM = 256, kTN = 256, kTK = 64;
 constexpr int kThreadsP = 256;
 constexpr int kBlocksM = kTM / 16, kBlocksN = kTN / 16;
-constexpr int kStageBytes = (kBlocksM + kBlocksN) * 1024;
-constexpr int kCtlBytes = 1024;
-constexpr int kLdsBytesP = kStages * kStageBytes + kCtlBytes;
+constexpr int kBlockBytes = 16 * kTK * 2;                 // 16 rows x 64 k: 2 KiB, a row is one 128-byte line
+constexpr int kHalfBytes = (kBlocksM + kBlocksN) / 2 * kBlockBytes;  // 8 X blocks + 8 W blocks: 32 KiB
+constexpr int kHalves = 5;                                // ring of half steps
+constexpr int kLdsBytesP = kHalves * kHalfBytes;
 constexpr int kAccTilesRows = 6;
 constexpr int kGroupM = 8;  // consecutive workgroups of an XCD walk 8 row tiles of one column tile
 
@@ -39,7 +40,8 @@ struct PParams {
   const int32_t* tenant_id;
   const uint8_t* route;
   AdapterView ad;
-  int64_t M;
+  int64_t M;         // rows of this launch
+  int64_t row_base;  // index of its first row in the caller's matrix (requests of unmapped rows)
   int d1, d2, site, B;
   int tilesM, tilesN;
 };
@@ -66,9 +68,9 @@ __device__ __forceinline__ void wait_vm() {
 __device__ __forceinline__ void mma_step(const unsigned char* sa, const unsigned char* sb, f32x4 (&acc)[8][8]) {
   bf16x8 a[8], b[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a[i] = *(const bf16x8*)(sa + i * 1024);
+  for (int i = 0; i < 8; ++i) a[i] = *(const bf16x8*)(sa + i * kBlockBytes);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) b[j] = *(const bf16x8*)(sb + j * 1024);
+  for (int j = 0; j < 8; ++j) b[j] = *(const bf16x8*)(sb + j * kBlockBytes);
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -97,28 +99,34 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
   const int KT = p.d1 / kTK;
   const uint32_t lds0 = lds_addr(lds);
 
-  // copies: waves 0,1 bring the 16 row blocks of X, waves 2,3 the 16 row blocks of W, 8 blocks each per k step
+  // copies.  A k step of 64 is brought in two halves: half 0 = X rows 0..127 and W rows 0..127 of the tile,
+  // half 1 = the other rows; a half is 8 + 8 blocks of 16 rows, a block two copy instructions of 8 rows each
+  // (8 lanes take the 128-byte line of a row, so every request is for whole cache lines).  Waves 0,1 bring
+  // the X blocks of a half (4 each), waves 2,3 the W blocks.  Which 16 bytes of the line a lane takes is
+  // permuted by the row so that the operand reads below spread over all LDS banks.
   const bool is_w = wave >= 2;
   const unsigned char* src = is_w ? (const unsigned char*)p.W : (const unsigned char*)p.X;
   const int64_t row0 = is_w ? (int64_t)n0 : m0;
   const int64_t rlim = is_w ? (int64_t)p.d2 : p.M;
-  uint32_t voff[8];
+  uint32_t voff[2][8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    // four consecutive lanes take the 64 bytes of one row (coalesced); which 16 of them a lane takes is
-    // permuted by the row so that the operand reads below spread over all LDS banks
-    const int rr = lane >> 2;
-    int64_t r = row0 + ((wave & 1) * 8 + j) * 16 + rr;
-    r = r < rlim ? r : rlim - 1;
-    voff[j] = (uint32_t)((uint64_t)r * (uint32_t)p.d1 * 2u + (uint32_t)((lane & 3) ^ ((rr >> 1) & 3)) * 16u);
-  }
-  auto issue = [&](int kt, int slot) __attribute__((always_inline)) {
-    const int kk = kt < KT ? kt : KT - 1;  // past the end: re-read the last step into a slot nobody reads
-    const unsigned char* b = src + (size_t)kk * (kTK * 2);
-    const uint32_t dst = lds0 + slot * kStageBytes + (wave * 8) * 1024;
+  for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      copy_to_lds(b, voff[j], dst + j * 1024);
+      const int rr = lane >> 3;
+      int64_t r = row0 + (hh * 8 + (wave & 1) * 4 + (j >> 1)) * 16 + (j & 1) * 8 + rr;
+      r = r < rlim ? r : rlim - 1;
+      voff[hh][j] = (uint32_t)((uint64_t)r * (uint32_t)p.d1 * 2u + (uint32_t)((lane & 7) ^ (rr & 7)) * 16u);
+    }
+  const uint32_t dst_in_half = (uint32_t)((is_w ? 8 : 0) + (wave & 1) * 4) * kBlockBytes;
+  // half H = 2 * (k step) + hh lives in ring slot H % kHalves
+  auto issue = [&](int kt, int hh, int slot) __attribute__((always_inline)) {
+    const int kk = kt < KT ? kt : KT - 1;  // past the end: re-read the last step into a slot nobody reads
+    const unsigned char* b = src + (size_t)kk * (kTK * 2);
+    const uint32_t dst = lds0 + slot * kHalfBytes + dst_in_half;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      copy_to_lds(b, voff[hh][j], dst + j * 1024);
     }
   };
 
@@ -128,22 +136,45 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // operand read: lane l takes row l % 16, k group l / 16 of a block stored as 16 rows x 64 bytes
-  const int rd_off = (lane & 15) * 64 + (((lane >> 4) ^ ((lane >> 1) & 3)) << 4);
-  const unsigned char* sa0 = lds + (wm * 8) * 1024 + rd_off;
-  const unsigned char* sb0 = lds + (kBlocksM + wn * 8) * 1024 + rd_off;
-
-  issue(0, 0);
-  issue(1, 1);
-  issue(2, 2);
-  auto step = [&](int kt, int slot) __attribute__((always_inline)) {
-    wait_vm<16>();                  // this wave's copies of step kt have landed
-    __builtin_amdgcn_s_barrier();   // so have the other waves'; and all waves are done reading step kt-1
-    asm volatile("" ::: "memory");
-    issue(kt + 3, (slot + 3) & 3);
-    mma_step(sa0 + slot * kStageBytes, sb0 + slot * kStageBytes, acc);
-    asm volatile("" ::: "memory");
+  // operand read: lane l takes row l % 16 and the 16 bytes of k group l / 16 of either k half of a block
+  const int rrow = lane & 15;
+  const int rd0 = rrow * 128 + ((((lane >> 4)) ^ (rrow & 7)) << 4);
+  const int rd1 = rrow * 128 + ((((lane >> 4) + 4) ^ (rrow & 7)) << 4);
+  const unsigned char* wbase = lds + (kBlocksM / 2) * kBlockBytes;
+  auto mma64 = [&](int slot_x, int slot_w) __attribute__((always_inline)) {
+    const unsigned char* sa = lds + slot_x * kHalfBytes;
+    const unsigned char* sb = wbase + slot_w * kHalfBytes;
+    // both k halves in one scheduling region: the operand reads of the second half are issued between the
+    // matrix instructions of the first
+    bf16x8 a0[8], b0[8], a1[8], b1[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a0[i] = *(const bf16x8*)(sa + rd0 + i * kBlockBytes);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b0[j] = *(const bf16x8*)(sb + rd0 + j * kBlockBytes);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a1[i] = *(const bf16x8*)(sa + rd1 + i * kBlockBytes);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b1[j] = *(const bf16x8*)(sb + rd1 + j * kBlockBytes);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0[j], a0[i], acc[i][j], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1[j], a1[i], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 64, 0);
   };
+
+  issue(0, 0, 0);
+  issue(0, 1, 1);
+  issue(1, 0, 2);
   // 48 of the 64 accumulator tiles in the accumulation registers, 16 in ordinary ones: with all 256 in the
   // accumulation file the compiler has no spare tile there and shuffles tiles between the files in the loop
 #pragma unroll
@@ -153,24 +184,33 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
       if (i < kAccTilesRows) asm volatile("" : "+a"(acc[i][j]));
       else asm volatile("" : "+v"(acc[i][j]));
     }
-  int kt = 0;
-  for (; kt + 4 <= KT; kt += 4) {
-    step(kt, 0);
-    step(kt + 1, 1);
-    step(kt + 2, 2);
-    step(kt + 3, 3);
+  int h0 = 0;  // ring slot of half 0 of the current step
+  for (int kt = 0; kt < KT; ++kt) {
+    const int h1 = h0 + 1 >= kHalves ? h0 + 1 - kHalves : h0 + 1;
+    const int h2 = h0 + 2 >= kHalves ? h0 + 2 - kHalves : h0 + 2;
+    const int h3 = h0 + 3 >= kHalves ? h0 + 3 - kHalves : h0 + 3;
+    const int h4 = h0 + 4 >= kHalves ? h0 + 4 - kHalves : h0 + 4;
+    wait_vm<8>();                   // all but the half issued last have landed: both halves of this step
+    __builtin_amdgcn_s_barrier();   // for every wave; and all waves are done reading the step before
+    asm volatile("" ::: "memory");
+    issue(kt + 1, 1, h3);
+    issue(kt + 2, 0, h4);
+    mma64(wm ? h1 : h0, wn ? h1 : h0);
+    asm volatile("" ::: "memory");
+    h0 = h2;
   }
-  for (int s = 0; kt < KT; ++kt, ++s) step(kt, s);
   wait_vm<0>();
   __syncthreads();
 
-  // ---- LoRA term of the routed rows as extra k steps ---------------------------------------------------
-  int* ctl = (int*)(lds + kStages * kStageBytes);
+  // ---- LoRA term of the routed rows as one more k step per 32 ranks ----------------------------------------
+  // t = X W^A (fp32) goes in as bf16 hi + lo: hi in the first k half of a block, lo in the second, against the
+  // same 32 rows of the tenant's W^B in both halves; rows of other tenants and unrouted rows enter as zeros.
+  int* ctl = (int*)(lds + 2 * kHalfBytes);  // ring slots 0 and 1 hold the operand blocks
   int my_ten = -1;
   {
     const int64_t m = m0 + tid;
     if (m < p.M) {
-      const int64_t req = p.row_to_req ? (int64_t)p.row_to_req[m] : m;
+      const int64_t req = p.row_to_req ? (int64_t)p.row_to_req[m] : p.row_base + m;
       int tenant = 0;
       const int r = (req >= 0 && req < p.B) ? routed_rank(p.ad, p.tenant_id, p.route, (int)req, p.B, p.site, &tenant) : 0;
       if (r) my_ten = tenant;
@@ -194,8 +234,10 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
     const bf16_t* Bm = (const bf16_t*)p.ad.B[cur * MILORA_NUM_SITES + p.site];
     const int64_t m = m0 + tid;
     const int n = n0 + tid;
+    // thread tid fills row tid of the X side and row tid of the W side
+    const uint32_t rb = (uint32_t)(tid & 15);
+    const uint32_t blk = (uint32_t)(tid >> 7) * kHalfBytes + (uint32_t)((tid >> 4) & 7) * kBlockBytes + rb * 128;
     for (int c0 = 0; c0 < r; c0 += 32) {
-      const uint32_t blk = (uint32_t)(tid >> 4) * 1024 + (uint32_t)(tid & 15) * 64;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x4 hi, lo, wb;
@@ -209,20 +251,20 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
             tv[h] = (my_ten == cur && c < r) ? p.t[(size_t)m * p.ad.r_max + c] : 0.f;
             bw[h] = (c < r && n < p.d2) ? (uint32_t)Bm[(size_t)c * p.d2 + n] : 0u;
           }
-          const bf16_t h0 = f32_to_bf16(tv[0]), h1 = f32_to_bf16(tv[1]);
-          hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-          lo[e] = pack_bf16x2(tv[0] - bf16_to_f32(h0), tv[1] - bf16_to_f32(h1));
+          const bf16_t h0b = f32_to_bf16(tv[0]), h1b = f32_to_bf16(tv[1]);
+          hi[e] = (uint32_t)h0b | ((uint32_t)h1b << 16);
+          lo[e] = pack_bf16x2(tv[0] - bf16_to_f32(h0b), tv[1] - bf16_to_f32(h1b));
           wb[e] = bw[0] | (bw[1] << 16);
         }
-        const uint32_t o = blk + ((g ^ ((tid >> 1) & 3)) << 4);
-        *(u32x4*)(lds + o) = hi;                              // slot 0, X side
-        *(u32x4*)(lds + kStageBytes + o) = lo;                // slot 1, X side
-        *(u32x4*)(lds + kBlocksM * 1024 + o) = wb;            // slot 0, W side
-        *(u32x4*)(lds + kStageBytes + kBlocksM * 1024 + o) = wb;  // slot 1, W side
+        const uint32_t o_hi = blk + (((uint32_t)g ^ (rb & 7)) << 4);
+        const uint32_t o_lo = blk + (((uint32_t)(g + 4) ^ (rb & 7)) << 4);
+        *(u32x4*)(lds + o_hi) = hi;
+        *(u32x4*)(lds + o_lo) = lo;
+        *(u32x4*)(lds + (kBlocksM / 2) * kBlockBytes + o_hi) = wb;
+        *(u32x4*)(lds + (kBlocksM / 2) * kBlockBytes + o_lo) = wb;
       }
       __syncthreads();
-      mma_step(sa0, sb0, acc);
-      mma_step(sa0 + kStageBytes, sb0 + kStageBytes, acc);
+      mma64(wm, wn);
       __syncthreads();
     }
     last = cur;
@@ -255,10 +297,7 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
 bool prefill_supported(int64_t M, int d1, int d2, const void* X, const void* W, const void* Y) {
   if (M < 64 || d1 % kTK != 0 || d2 % 16 != 0) return false;
   if ((((uintptr_t)X | (uintptr_t)W) & 15) != 0 || ((uintptr_t)Y & 7) != 0) return false;
-  const uint64_t rows = (uint64_t)(M > d2 ? M : d2);
-  if (rows * (uint64_t)d1 * 2u >= (1ull << 32)) return false;  // 32-bit byte offsets inside X and W
-  const int64_t tiles = ((M + kTM - 1) / kTM) * ((d2 + kTN - 1) / kTN);
-  return tiles < (1 << 28);
+  return (uint64_t)d2 * (uint64_t)d1 * 2u < (1ull << 32);  // 32-bit byte offsets inside W (X is cut into row slices)
 }
 
 int routed_linear_prefill(const bf16_t* X, int64_t M, int d1, int d2, const int32_t* row_to_req, const bf16_t* W,
@@ -271,16 +310,38 @@ int routed_linear_prefill(const bf16_t* X, int64_t M, int d1, int d2, const int3
     MILORA_HIP(hipFuncSetAttribute((const void*)prefill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesP));
     lds_set_for = dev;
   }
-  PParams p;
-  p.X = X; p.W = W; p.bias = bias; p.Y = Y; p.t = t;
-  p.row_to_req = row_to_req; p.tenant_id = tenant_id; p.route = route; p.ad = ad;
-  p.M = M; p.d1 = d1; p.d2 = d2; p.site = site; p.B = B;
-  p.tilesM = (int)((M + kTM - 1) / kTM);
-  p.tilesN = (d2 + kTN - 1) / kTN;
-  const int total = p.tilesM * p.tilesN;
-  const int per = (total + 7) / 8;
-  hipLaunchKernelGGL(prefill_kernel, dim3(8 * per), dim3(kThreadsP), kLdsBytesP, stream, p);
-  return check_launch();
+  // rows are independent: slices whose byte offsets inside X fit 32 bits and whose tile count fits a launch
+  int64_t slice = (int64_t)(((1ull << 32) - 1) / ((uint64_t)d1 * 2u)) / kTM * kTM;
+  const int tilesN = (d2 + kTN - 1) / kTN;
+  const int64_t by_grid = (int64_t)((1 << 24) / tilesN) * kTM;
+  if (slice > by_grid) slice = by_grid;
+  if (slice < kTM) return MILORA_EUNSUPPORTED;
+  for (int64_t r0 = 0; r0 < M; r0 += slice) {
+    PParams p;
+    p.M = M - r0 < slice ? M - r0 : slice;
+    p.X = X + (size_t)r0 * d1;
+    p.W = W;
+    p.bias = bias;
+    p.Y = Y + (size_t)r0 * d2;
+    p.t = t + (size_t)r0 * ad.r_max;
+    p.row_to_req = row_to_req ? row_to_req + r0 : nullptr;
+    p.row_base = r0;
+    p.tenant_id = tenant_id;
+    p.route = route;
+    p.ad = ad;
+    p.d1 = d1;
+    p.d2 = d2;
+    p.site = site;
+    p.B = B;
+    p.tilesM = (int)((p.M + kTM - 1) / kTM);
+    p.tilesN = tilesN;
+    const int total = p.tilesM * p.tilesN;
+    const int per = (total + 7) / 8;
+    hipLaunchKernelGGL(prefill_kernel, dim3(8 * per), dim3(kThreadsP), kLdsBytesP, stream, p);
+    const int rc = check_launch();
+    if (rc) return rc;
+  }
+  return MILORA_OK;
 }
 
 }  // namespace milora

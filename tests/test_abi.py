@@ -45,6 +45,24 @@ def test_workspace_sizes_are_monotone_and_reject_bad_sizes():
     assert mb.routed_linear_workspace_bytes(32768, 4096, 4096, 32) >= 32768 * 32 * 4
 
 
+def test_kernel_choice_of_the_routed_linear():
+    import torch
+
+    k = mb.milora_routed_linear_kernel
+    assert k(32, 4096, 4096, torch.bfloat16, mb.W_PACKED) == mb.KERNEL_STREAM
+    assert k(32768, 4096, 11008, torch.bfloat16, mb.W_PACKED) == mb.KERNEL_STREAM
+    assert k(32768, 4096, 11008, torch.bfloat16) == mb.KERNEL_TILES
+    assert k(32768, 11008, 4096, torch.bfloat16) == mb.KERNEL_TILES
+    assert k(64, 64, 16, torch.bfloat16) == mb.KERNEL_TILES
+    assert k(63, 64, 16, torch.bfloat16) == mb.KERNEL_GENERIC  # few rows
+    assert k(700, 96, 528, torch.bfloat16) == mb.KERNEL_GENERIC  # reduction not a multiple of 64
+    assert k(700, 192, 520, torch.bfloat16) == mb.KERNEL_GENERIC  # width not a multiple of 16
+    assert k(700, 192, 528, torch.float32) == mb.KERNEL_GENERIC
+    assert k(1 << 20, 4096, 4096, torch.bfloat16) == mb.KERNEL_TILES  # in row slices with 32-bit byte offsets
+    assert k(32, 4096, 4096, torch.float32, mb.W_PACKED) == -3
+    assert k(0, 8, 8, torch.float32) == -1 and k(8, 8, 8, torch.float32, 5) == -1
+
+
 def test_argument_validation_happens_before_any_device_work():
     L = mb.lib()
     null = ctypes.c_void_p(None)

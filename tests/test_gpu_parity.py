@@ -219,8 +219,10 @@ def test_routed_linear_many_rows_matrix_core_tiles(site):
     """Row-major bf16 weights with several hundred rows take the matrix-core tile kernel: three row tiles with
     a ragged last one, one to three column tiles with a ragged last one, prompts of several tenants (ranks
     5..64) meeting inside a tile, bias on two of the sites."""
-    wl = small(dtype="bf16", d=160, F=544, T=5, B=9, ranks=(5, 16, 32, 64), tenants="uniform", seed=31)
+    wl = small(dtype="bf16", d=192, F=576, T=5, B=9, ranks=(5, 16, 32, 64), tenants="uniform", seed=31)
     M = 700
+    d1, d2 = synth.site_dims(site, wl.d, wl.F)
+    assert mb.milora_routed_linear_kernel(M, d1, d2, torch.bfloat16) == mb.KERNEL_TILES
     Y, ref = _linear_case(wl, site, M=M, row_to_req=_segments(M, wl.B, site), with_bias=(site in (2, 6)), seed=site)
     assert_rows_close(Y, ref, torch.bfloat16, f"site {site}")
 
@@ -229,6 +231,7 @@ def test_routed_linear_many_rows_scattered_requests_and_repeatability():
     wl = small(dtype="bf16", d=256, F=352, T=6, B=20, ranks=(8, 24), tenants="uniform", seed=32)
     g = torch.Generator().manual_seed(5)
     r2r = torch.randint(0, wl.B, (300,), generator=g)  # neighbouring rows of different requests
+    assert mb.milora_routed_linear_kernel(300, 256, 352, torch.bfloat16) == mb.KERNEL_TILES
     Y, ref = _linear_case(wl, 5, M=300, row_to_req=r2r, with_bias=True, seed=1)
     assert_rows_close(Y, ref, torch.bfloat16)
     Y2, _ = _linear_case(wl, 5, M=300, row_to_req=r2r, with_bias=True, seed=1)
@@ -251,12 +254,42 @@ def test_routed_linear_many_rows_small_integers_bit_exact():
     route = torch.tensor([site, 0, site, site, 3, site], dtype=torch.uint8)
     r2r = _segments(M, B, 9)
     tab = mb.AdapterTable.from_tensors(A, Bm, [r] * T)
+    assert mb.milora_routed_linear_kernel(M, d1, d2, torch.bfloat16) == mb.KERNEL_TILES
     Y = mb.milora_routed_linear(X, W, tab, site, tid.to(DEV), route.to(DEV), row_to_req=r2r.to(DEV), d2=d2)
     ref = oracle.routed_linear(np_of(X), np_of(W), oracle.Adapters(
         [[np_of(a) for a in row] for row in A], [[np_of(b) for b in row] for row in Bm], [r] * T),
         site, tid.numpy(), route.numpy(), row_to_req=r2r.numpy())
     assert np.abs(ref).max() <= 256
     np.testing.assert_array_equal(to_f64(Y), ref)
+
+
+def test_routed_linear_many_rows_beyond_32_bit_offsets():
+    """X larger than 4 GiB: the launcher cuts the rows into slices whose byte offsets fit 32 bits."""
+    d1, d2, M = 11008, 16, 200_000
+    wl = small(dtype="bf16", d=d2, F=d1, T=3, B=5, ranks=(8,), tenants="uniform", seed=33)
+    W, ad, tab = device_layer(wl)
+    site = 6  # F -> d
+    assert mb.milora_routed_linear_kernel(M, d1, d2, torch.bfloat16) == mb.KERNEL_TILES
+    tid = synth.tenant_ids(wl)
+    route = torch.tensor([6, 6, 0, 6, 6], dtype=torch.uint8)
+    r2r = (torch.arange(M) * wl.B // M).to(torch.int32)
+    X = torch.empty(M, d1, dtype=torch.bfloat16, device=DEV)
+    gx = torch.Generator(device=DEV).manual_seed(7)
+    for a in range(0, M, 20_000):
+        X[a:a + 20_000] = torch.empty(20_000, d1, dtype=torch.float32, device=DEV).normal_(0, 1, generator=gx)
+    Y = mb.milora_routed_linear(X, W[site], tab, site, tid.to(DEV), route.to(DEV), row_to_req=r2r.to(DEV), d2=d2)
+    cut = ((1 << 32) - 1) // (d1 * 2) // 256 * 256  # first row of the second slice
+    rows = torch.tensor([0, 1, cut - 1, cut, cut + 1, cut + 255, cut + 256, M - 2, M - 1, 77_777, 150_001])
+    ref = oracle.routed_linear(np_of(X[rows.to(DEV)]), np_of(W[site]), oracle_adapters(ad), site, tid.numpy(),
+                               route.numpy(), row_to_req=r2r[rows].numpy())
+    assert_rows_close(Y[rows.to(DEV)], ref, torch.bfloat16)
+
+
+def test_measurement_helpers_report_plausible_rates():
+    buf = torch.empty(1 << 29, dtype=torch.uint8, device=DEV).zero_()
+    gbs = mb.milora_measure_read_rate(buf, reps=3)
+    tf = mb.milora_measure_matrix_rate(500, DEV)
+    assert 500 < gbs < 20000 and 100 < tf < 5000
 
 
 def test_prefill_shape_sampled_rows_full_size():
@@ -276,6 +309,7 @@ def test_prefill_shape_sampled_rows_full_size():
                       torch.randint(0, M, (41,), generator=g)]).unique()
     for site in range(7):
         d1, d2 = synth.site_dims(site, wl.d, wl.F)
+        assert mb.milora_routed_linear_kernel(M, d1, d2, torch.bfloat16) == mb.KERNEL_TILES
         route[site] = site  # every site has at least one routed prompt (requests 0..6)
         gx = torch.Generator(device=DEV).manual_seed(500 + site)
         X = torch.empty(M, d1, dtype=torch.float32, device=DEV).normal_(0, 1, generator=gx).to(torch.bfloat16)
