@@ -19,6 +19,8 @@ size_t routed_linear_packed_workspace_bytes(int M, int d1, int d2, int r_max);
 int pack_weight(const void* src, void* dst, int d1, int d2, hipStream_t st);
 // prefill.hip
 bool prefill_supported(int64_t M, int d1, int d2, const void* X, const void* W, const void* Y);
+int launch_shrink_tiles(const bf16_t* X, int64_t M, int d1, const int32_t* row_to_req, const AdapterView& ad, int site,
+                        const int32_t* tenant_id, const uint8_t* route, int B, float* t, hipStream_t stream);
 int routed_linear_prefill(const bf16_t* X, int64_t M, int d1, int d2, const int32_t* row_to_req, const bf16_t* W,
                           const bf16_t* bias, const AdapterView& ad, int site, const int32_t* tenant_id,
                           const uint8_t* route, int B, const float* t, bf16_t* Y, hipStream_t st);
@@ -259,11 +261,14 @@ extern "C" int milora_routed_linear(const void* X, int64_t M, int d1, int d2, in
     return MILORA_OK;
   }
   float* t = (float*)workspace;
-  rc = launch_shrink(X, M, d1, dtype, row_to_req, ad, site, tenant_id, route, B, t, st);
-  if (rc) return rc;
-  if (dtype == MILORA_BF16 && prefill_supported(M, d1, d2, X, W, Y))
+  if (dtype == MILORA_BF16 && prefill_supported(M, d1, d2, X, W, Y)) {
+    rc = launch_shrink_tiles((const bf16_t*)X, M, d1, row_to_req, ad, site, tenant_id, route, B, t, st);
+    if (rc) return rc;
     return routed_linear_prefill((const bf16_t*)X, M, d1, d2, row_to_req, (const bf16_t*)W, (const bf16_t*)bias, ad,
                                  site, tenant_id, route, B, t, (bf16_t*)Y, st);
+  }
+  rc = launch_shrink(X, M, d1, dtype, row_to_req, ad, site, tenant_id, route, B, t, st);
+  if (rc) return rc;
   return launch_linear_generic(X, M, d1, d2, dtype, row_to_req, W, bias, ad, site, tenant_id, route, B, t, Y, st);
 }
 

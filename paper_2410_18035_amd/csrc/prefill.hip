@@ -19,6 +19,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// Adapter matrices are reached through pointer tables read at run time; telling the compiler that they lie in
+// global memory keeps their loads off the counter the LDS reads wait on.
+typedef __attribute__((address_space(1))) const bf16_t gbf16;
+__device__ __forceinline__ gbf16* in_global(const void* p) { return (gbf16*)p; }
 
 constexpr int kTM = 256, kTN = 256, kTK = 64;
 constexpr int kThreadsP = 256;
@@ -231,7 +235,7 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
     const int cur = ctl[0];
     if (cur == 0x7fffffff) break;
     const int r = p.ad.rank[cur];
-    const bf16_t* Bm = (const bf16_t*)p.ad.B[cur * MILORA_NUM_SITES + p.site];
+    gbf16* Bm = in_global(p.ad.B[cur * MILORA_NUM_SITES + p.site]);
     const int64_t m = m0 + tid;
     const int n = n0 + tid;
     // thread tid fills row tid of the X side and row tid of the W side
@@ -292,6 +296,109 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
   }
 }
 
+// ---- LoRA shrink for many rows: t[m][0..r) = X[m] . W^A of the row's tenant, routed rows only --------------
+// One workgroup per 64 rows, 16 per wave.  W^A is [d1][r] (reduction index outermost), the matrix cores
+// want 8 consecutive reduction indices per lane, so 256-row chunks of W^A go through LDS and are read back
+// column-wise; X rows come straight from global memory as operands, a chunk's worth at a time.  A tile
+// whose rows belong to several tenants is computed once per tenant and each row keeps its own tenant's
+// result.  Needs d1 % 32 == 0.
+constexpr int kShrinkRows = 64, kShrinkK = 256, kShrinkC = 64;
+constexpr int kShrinkLd = 66;  // LDS row of 64 columns padded: the 4 k groups of a column read hit distinct banks
+
+__global__ void __launch_bounds__(256, 2) shrink_tiles_kernel(const bf16_t* __restrict__ X, int64_t M, int64_t row_base,
+                                                              int d1, const int32_t* __restrict__ row_to_req,
+                                                              AdapterView ad, int site,
+                                                              const int32_t* __restrict__ tenant_id,
+                                                              const uint8_t* __restrict__ route, int B,
+                                                              float* __restrict__ t) {
+  __shared__ bf16_t As[kShrinkK][kShrinkLd];
+  __shared__ int row_ten[kShrinkRows];
+  __shared__ int next_ten;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t m0 = (int64_t)blockIdx.x * kShrinkRows;
+  if (tid < kShrinkRows) {
+    const int64_t m = m0 + tid;
+    int ten = -1;
+    if (m < M) {
+      const int64_t req = row_to_req ? (int64_t)row_to_req[m] : row_base + m;
+      int tenant = 0;
+      if (req >= 0 && req < B && routed_rank(ad, tenant_id, route, (int)req, B, site, &tenant)) ten = tenant;
+    }
+    row_ten[tid] = ten;
+  }
+  __syncthreads();
+  const int my_row = wave * 16 + (lane & 15);
+  int64_t xrow = m0 + my_row;
+  xrow = xrow < M ? xrow : M - 1;
+  const bf16_t* xp = X + (size_t)xrow * d1 + (lane >> 4) * 8;
+  int last = -1;
+  for (;;) {
+    if (tid == 0) next_ten = 0x7fffffff;
+    __syncthreads();
+    if (tid < kShrinkRows && row_ten[tid] > last) atomicMin(&next_ten, row_ten[tid]);
+    __syncthreads();
+    const int cur = next_ten;
+    if (cur == 0x7fffffff) break;
+    const int r = ad.rank[cur];
+    gbf16* A = in_global(ad.A[cur * MILORA_NUM_SITES + site]);
+    for (int cb = 0; cb < r; cb += kShrinkC) {
+      const int rc = r - cb < kShrinkC ? r - cb : kShrinkC;
+      const int ntile = (rc + 15) >> 4;
+      f32x4 acc[4];
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      // this thread stages column c of every fourth row of a chunk; columns past the rank and rows past d1
+      // read a valid element instead (what they produce is never stored / never used)
+      const int c = tid & 63;
+      gbf16* ap = A + cb + (c < rc ? c : 0);
+      for (int k0 = 0; k0 < d1; k0 += kShrinkK) {
+        const int steps = d1 - k0 < kShrinkK ? (d1 - k0) / 32 : kShrinkK / 32;
+        bf16x8 xf[kShrinkK / 32];
+#pragma unroll
+        for (int ks = 0; ks < kShrinkK / 32; ++ks) xf[ks] = *(const bf16x8*)(xp + k0 + (ks < steps ? ks : 0) * 32);
+        __syncthreads();  // the chunk before has been read
+#pragma unroll 16
+        for (int i = 0; i < kShrinkK / 4; ++i) {
+          int k = k0 + (tid >> 6) + 4 * i;
+          k = k < d1 ? k : d1 - 1;
+          As[(tid >> 6) + 4 * i][c] = ap[(size_t)k * r];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < kShrinkK / 32; ++ks) {
+          if (ks < steps) {
+            const int kk0 = ks * 32 + (lane >> 4) * 8;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+              if (nt < ntile) {
+                u32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  w[e] = (uint32_t)As[kk0 + 2 * e][nt * 16 + (lane & 15)] |
+                         ((uint32_t)As[kk0 + 2 * e + 1][nt * 16 + (lane & 15)] << 16);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), xf[ks], acc[nt], 0, 0, 0);
+              }
+            }
+          }
+        }
+      }
+      __syncthreads();
+      // lane holds row lane % 16 of the wave, columns (lane / 16) * 4 .. + 4 of each 16-column tile
+      const int64_t m = m0 + my_row;
+      if (m < M && row_ten[my_row] == cur) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int cc = cb + nt * 16 + (lane >> 4) * 4 + e;
+            if (nt < ntile && cc < r) t[(size_t)m * ad.r_max + cc] = acc[nt][e];
+          }
+      }
+    }
+    last = cur;
+  }
+}
+
 }  // namespace
 
 bool prefill_supported(int64_t M, int d1, int d2, const void* X, const void* W, const void* Y) {
@@ -338,6 +445,21 @@ int routed_linear_prefill(const bf16_t* X, int64_t M, int d1, int d2, const int3
     const int total = p.tilesM * p.tilesN;
     const int per = (total + 7) / 8;
     hipLaunchKernelGGL(prefill_kernel, dim3(8 * per), dim3(kThreadsP), kLdsBytesP, stream, p);
+    const int rc = check_launch();
+    if (rc) return rc;
+  }
+  return MILORA_OK;
+}
+
+// LoRA shrink of the rows the tile kernel serves (same conditions as prefill_supported).
+int launch_shrink_tiles(const bf16_t* X, int64_t M, int d1, const int32_t* row_to_req, const AdapterView& ad, int site,
+                        const int32_t* tenant_id, const uint8_t* route, int B, float* t, hipStream_t stream) {
+  const int64_t slice = (int64_t)1 << 30;  // rows per launch: the grid index stays well inside 32 bits
+  for (int64_t r0 = 0; r0 < M; r0 += slice) {
+    const int64_t mc = M - r0 < slice ? M - r0 : slice;
+    hipLaunchKernelGGL(shrink_tiles_kernel, dim3((unsigned)((mc + kShrinkRows - 1) / kShrinkRows)), dim3(256), 0, stream,
+                       X + (size_t)r0 * d1, mc, r0, d1, row_to_req ? row_to_req + r0 : nullptr, ad, site, tenant_id,
+                       route, B, t + (size_t)r0 * ad.r_max);
     const int rc = check_launch();
     if (rc) return rc;
   }

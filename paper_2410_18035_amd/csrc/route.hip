@@ -107,18 +107,23 @@ __device__ __forceinline__ float activate(float x, int act) {
   }
 }
 
-// One workgroup per request: h (mean of the partial sums, or the last valid row), z = g(h),
-// logits_j = z . Wr[t][j], route = index of the largest logit (lowest index on equality).
+// One workgroup of 1024 threads per request: h (mean of the partial sums, or the last valid row), z = g(h),
+// logits_j = z . Wr[t][j], route = index of the largest logit (lowest index on equality).  A thread owns four
+// neighbouring columns; the S partial sums of a column are added as eight interleaved running sums (slice s
+// goes to sum s % 8) that are combined pairwise at the end, so eight loads are in flight and the order is fixed.
+constexpr int kFinishThreads = 1024;
+constexpr int kFinishWays = 8;
+
 template <typename T>
-__global__ void __launch_bounds__(kThreads) route_finish_kernel(const T* __restrict__ H, int64_t M_tok, int d,
-                                                                const int32_t* __restrict__ seq_start,
-                                                                const int32_t* __restrict__ seq_len,
-                                                                const int32_t* __restrict__ tenant_id, int T_tenants,
-                                                                const T* __restrict__ Wr, int pool, int act, int S,
-                                                                const float* __restrict__ partial,
-                                                                uint8_t* __restrict__ route_out,
-                                                                float* __restrict__ logits_out) {
-  __shared__ float wsum[kThreads / 64][MILORA_NUM_SITES];
+__global__ void __launch_bounds__(kFinishThreads) route_finish_kernel(const T* __restrict__ H, int64_t M_tok, int d,
+                                                                      const int32_t* __restrict__ seq_start,
+                                                                      const int32_t* __restrict__ seq_len,
+                                                                      const int32_t* __restrict__ tenant_id,
+                                                                      int T_tenants, const T* __restrict__ Wr, int pool,
+                                                                      int act, int S, const float* __restrict__ partial,
+                                                                      uint8_t* __restrict__ route_out,
+                                                                      float* __restrict__ logits_out) {
+  __shared__ float wsum[kFinishThreads / 64][MILORA_NUM_SITES];
   const int b = blockIdx.x;
   const int64_t start = seq_start[b], n = seq_len[b];
   const int t = tenant_id[b];
@@ -133,18 +138,43 @@ __global__ void __launch_bounds__(kThreads) route_finish_kernel(const T* __restr
   for (int j = 0; j < MILORA_NUM_SITES; ++j) acc[j] = 0.f;
   const T* w = Wr + (size_t)t * MILORA_NUM_SITES * d;
   const float inv_n = 1.0f / (float)n;
-  for (int i = threadIdx.x; i < d; i += kThreads) {
-    float h;
+  const bool vec = (d % 4) == 0;  // rows of `partial` are then 16-byte aligned
+  const float* pb = partial + (size_t)b * S * d;
+  for (int i0 = threadIdx.x * 4; i0 < d; i0 += kFinishThreads * 4) {
+    const int nv = d - i0 < 4 ? d - i0 : 4;
+    float h[4] = {0.f, 0.f, 0.f, 0.f};
     if (pool == MILORA_POOL_LAST) {
-      h = Elem<T>::load(H, (size_t)(start + n - 1) * d + i);
+      for (int v = 0; v < nv; ++v) h[v] = Elem<T>::load(H, (size_t)(start + n - 1) * d + i0 + v);
     } else {
-      float sum = 0.f;
-      for (int s = 0; s < S; ++s) sum += partial[((size_t)b * S + s) * d + i];
-      h = sum * inv_n;
-    }
-    const float z = activate(h, act);
+      float run[kFinishWays][4];
 #pragma unroll
-    for (int j = 0; j < MILORA_NUM_SITES; ++j) acc[j] += z * Elem<T>::load(w, (size_t)j * d + i);
+      for (int u = 0; u < kFinishWays; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) run[u][v] = 0.f;
+      for (int s0 = 0; s0 < S; s0 += kFinishWays) {
+#pragma unroll
+        for (int u = 0; u < kFinishWays; ++u) {
+          if (s0 + u < S) {
+            const float* q = pb + (size_t)(s0 + u) * d + i0;
+            if (vec) {
+              const float4 x = *reinterpret_cast<const float4*>(q);
+              run[u][0] += x.x; run[u][1] += x.y; run[u][2] += x.z; run[u][3] += x.w;
+            } else {
+              for (int v = 0; v < nv; ++v) run[u][v] += q[v];
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        h[v] = (((run[0][v] + run[1][v]) + (run[2][v] + run[3][v])) +
+                ((run[4][v] + run[5][v]) + (run[6][v] + run[7][v]))) * inv_n;
+    }
+    for (int v = 0; v < nv; ++v) {
+      const float z = activate(h[v], act);
+#pragma unroll
+      for (int j = 0; j < MILORA_NUM_SITES; ++j) acc[j] += z * Elem<T>::load(w, (size_t)j * d + i0 + v);
+    }
   }
 #pragma unroll
   for (int j = 0; j < MILORA_NUM_SITES; ++j) {
@@ -158,7 +188,7 @@ __global__ void __launch_bounds__(kThreads) route_finish_kernel(const T* __restr
     int best = 0;
     for (int j = 0; j < MILORA_NUM_SITES; ++j) {
       float v = 0.f;
-      for (int wv = 0; wv < kThreads / 64; ++wv) v += wsum[wv][j];
+      for (int wv = 0; wv < kFinishThreads / 64; ++wv) v += wsum[wv][j];
       logit[j] = v;
       if (v > logit[best]) best = j;
       if (logits_out) logits_out[b * MILORA_NUM_SITES + j] = v;
@@ -223,11 +253,11 @@ extern "C" int milora_route(const void* H, int64_t M_tok, int d, int dtype, cons
     if (rc != MILORA_OK) return rc;
   }
   if (dtype == MILORA_BF16)
-    hipLaunchKernelGGL((route_finish_kernel<bf16_t>), dim3(B), dim3(kThreads), 0, st, (const bf16_t*)H, M_tok, d,
+    hipLaunchKernelGGL((route_finish_kernel<bf16_t>), dim3(B), dim3(kFinishThreads), 0, st, (const bf16_t*)H, M_tok, d,
                        seq_start, seq_len, tenant_id, n_tenants, (const bf16_t*)Wr, pool, act, S, partial, route_out,
                        logits_out);
   else
-    hipLaunchKernelGGL((route_finish_kernel<float>), dim3(B), dim3(kThreads), 0, st, (const float*)H, M_tok, d,
+    hipLaunchKernelGGL((route_finish_kernel<float>), dim3(B), dim3(kFinishThreads), 0, st, (const float*)H, M_tok, d,
                        seq_start, seq_len, tenant_id, n_tenants, (const float*)Wr, pool, act, S, partial, route_out,
                        logits_out);
   return check_launch();
