@@ -108,6 +108,68 @@ def prefill_leg(torch, mb, synth, dev, reps=5):
             "route_pool_gbs": round(valid_bytes / (route_ms * 1e-3) / 1e9, 1)}
 
 
+def stack_bench(args, torch, mb, synth, wl, dev):
+    """Multi-layer decode stacks (not the headline workload): every layer's packed weights and adapters resident
+    in HBM, routes as a given table, one step = one token for all B requests through all L layers."""
+    tid = synth.tenant_ids(wl).to(dev)
+    table = synth.constructed_routes(wl).to(dev)
+    layers, nbytes = [], 0
+    for layer in range(wl.L):
+        W = synth.base_weights(wl, layer, dev)
+        Wp = [mb.milora_pack_weight(w) for w in W]
+        del W
+        ad = synth.adapters(wl, layer, dev)
+        tab = mb.AdapterTable.from_tensors(ad.A, ad.B, ad.rank)
+        layers.append((Wp, ad, tab))
+        nbytes += algorithmic_bytes(wl, table[layer].cpu().numpy(), tid.cpu().numpy(), ad.rank)["layer_step"]
+    ws = torch.zeros(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, max(wl.ranks)), dtype=torch.uint8, device=dev)
+    x0 = synth.decode_input(wl, 0, dev)
+    bufs = [torch.empty_like(x0), torch.empty_like(x0)]
+    qkv = torch.empty(wl.B, 3 * wl.d, dtype=x0.dtype, device=dev)
+
+    def step():
+        x = x0
+        for layer, (Wp, ad, tab) in enumerate(layers):
+            y = bufs[layer & 1]
+            mb.milora_layer_decode(x, Wp, tab, tid, table[layer], wl.F, w_layout=mb.W_PACKED, rmsnorm=wl.rmsnorm, y=y,
+                                   qkv_out=qkv, workspace=ws)
+            x = y
+
+    step()
+    torch.cuda.synchronize()
+    run = step
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    achieved = nbytes / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "routed-LoRA decode tokens/s through the layer stack + % HBM roofline", "value": round(wl.B / (ms * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.L, "d": wl.d, "ffn": wl.F, "batch": wl.B, "tenants": wl.T,
+                   "ranks": list(wl.ranks), "routes": "constructed table", "hip_graph": not args.no_graph},
+        "roofline": {"bound": "hbm", "kernel": "decode_stream_kernel (L launches per step)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_step": nbytes, "us_per_layer": round(ms * 1e3 / wl.L, 2)},
+        "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,7 +201,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.CONFIGS[args.workload]
-    assert wl.L == 1 and wl.dtype == "bf16", "the benchmark runs the single-layer bf16 configurations"
+    assert wl.dtype == "bf16" and wl.decode_steps > 0, "the benchmark runs the bf16 decode configurations"
+    if wl.L > 1:
+        stack_bench(args, torch, mb, synth, wl, dev)
+        return
     nsteps = wl.decode_steps
 
     # ---- inputs, resident in HBM -----------------------------------------------------------------

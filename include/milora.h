@@ -55,8 +55,12 @@ typedef enum {
 } milora_status;
 
 typedef enum { MILORA_BF16 = 0, MILORA_F32 = 1 } milora_dtype;
-typedef enum { MILORA_POOL_MEAN = 0, MILORA_POOL_LAST = 1 } milora_pool;
-typedef enum { MILORA_ACT_IDENTITY = 0, MILORA_ACT_TANH = 1, MILORA_ACT_RELU = 2, MILORA_ACT_GELU = 3 } milora_act;
+/* Poolers of Sec. 3.3: average, last token, max, self-attention (App. C). */
+typedef enum { MILORA_POOL_MEAN = 0, MILORA_POOL_LAST = 1, MILORA_POOL_MAX = 2, MILORA_POOL_SELFATTN = 3 } milora_pool;
+/* Router activation g: fixed functions, or the rational form of Sec. 3.4 with the caller's coefficients. */
+typedef enum {
+  MILORA_ACT_IDENTITY = 0, MILORA_ACT_TANH = 1, MILORA_ACT_RELU = 2, MILORA_ACT_GELU = 3, MILORA_ACT_RATIONAL = 4
+} milora_act;
 
 /* Storage of a base weight W (math shape d1 x d2).
  *  MILORA_W_ROWMAJOR : [d2][d1], d1 contiguous (the usual linear-layer storage).
@@ -97,7 +101,8 @@ int milora_last_hip_error(void);
 
 /* ------------------------------------------------------------------------------------------------
  * milora_route - the prompt-aware LoRA router of one layer (Sec. 3.3):
- *   h_b = Pooler(H^l restricted to request b's prompt tokens)        (Eq. 2; last-token / average)
+ *   h_b = Pooler(H^l restricted to request b's prompt tokens)        (Eq. 2; last-token / average / max /
+ *                                                                     self-attention: softmax_t(H w_sa)^T H, App. C)
  *   route[b] = argmax_j ( g(h_b) W_r^{l, tenant(b)} )_j               (Eq. 3 with top-1)
  * Softmax is increasing, so the top-1 expert is taken on the logits; equal logits resolve to the
  * lowest index.  Pooled state, activation and logits are kept in fp32 whatever `dtype` is.
@@ -109,18 +114,24 @@ int milora_last_hip_error(void);
  *   tenant_id  device [B] int32 in [0, T)
  *   Wr         device [T][7][d], `dtype`: column j of tenant t's d x 7 router matrix is the
  *              contiguous d-vector Wr[t][j]; no bias
+ *   w_sa       device [T][d], `dtype`: the self-attention pooler's query vector of each tenant for this layer;
+ *              read for MILORA_POOL_SELFATTN only, NULL otherwise.  d <= 8192 for this pooler.
+ *   act_coef   HOST [12] float: a_0..a_6, b_1..b_5 of Ra(x) = (sum_j a_j x^j) / (1 + |sum_i b_i x^i|)
+ *              (Sec. 3.4; one set per call, i.e. per layer); read for MILORA_ACT_RATIONAL only, NULL otherwise
  *   route_out  device [B] uint8: selected site per request (row `l` of the caller's route table)
  *   logits_out device [B][7] float or NULL: the seven logits
  *   workspace  device, milora_route_workspace_bytes(B, d, M_tok) bytes
  * A request whose span leaves [0, M_tok), whose length is < 1 or whose tenant id is out of range
  * gets route MILORA_ROUTE_NONE and NaN logits; the others are unaffected.
- * Errors: EINVAL (null pointers, B/d/T/M_tok < 1, bad enums), EWORKSPACE, EHIP.
+ * Errors: EINVAL (null pointers, B/d/T/M_tok < 1, bad enums, w_sa / act_coef missing where needed), ERANGE
+ * (B > 65535; self-attention pooling with d > 8192), EWORKSPACE, EHIP.
  */
 size_t milora_route_workspace_bytes(int B, int d, int64_t M_tok);
 int milora_route(const void *H, int64_t M_tok, int d, int dtype, const int32_t *seq_start,
                  const int32_t *seq_len, const int32_t *tenant_id, int B, int n_tenants,
-                 const void *Wr, int pool, int act, uint8_t *route_out, float *logits_out,
-                 void *workspace, size_t workspace_bytes, void *stream);
+                 const void *Wr, int pool, int act, const void *w_sa, const float *act_coef,
+                 uint8_t *route_out, float *logits_out, void *workspace, size_t workspace_bytes,
+                 void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * milora_routed_linear - one LoRA-carrying linear for M rows (Eq. 1 with the layer-level gate of

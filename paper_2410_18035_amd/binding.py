@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(_HERE, "_lib", "libmilora.so")
 
 NUM_SITES = 7
 BF16, F32 = 0, 1
-POOL = {"mean": 0, "last": 1}
-ACT = {"identity": 0, "tanh": 1, "relu": 2, "gelu": 3}
+POOL = {"mean": 0, "last": 1, "max": 2, "selfattn": 3}
+ACT = {"identity": 0, "tanh": 1, "relu": 2, "gelu": 3, "rational": 4}
 W_ROWMAJOR, W_PACKED = 0, 1
 LAYER_RMSNORM = 1
 ROUTE_NONE = 255
@@ -71,7 +71,8 @@ def lib() -> ctypes.CDLL:
         L.milora_route_workspace_bytes.restype = sz
         L.milora_route_workspace_bytes.argtypes = [i32, i32, i64]
         L.milora_route.restype = i32
-        L.milora_route.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+        L.milora_route.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, i32, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_float),
+                                   vp, vp, vp, sz, vp]
         L.milora_routed_linear_workspace_bytes.restype = sz
         L.milora_routed_linear_workspace_bytes.argtypes = [i64, i32, i32, i32]
         L.milora_routed_linear_kernel.restype = i32
@@ -181,8 +182,11 @@ def route_workspace_bytes(B: int, d: int, M_tok: int) -> int:
 def milora_route(H: torch.Tensor, seq_start: torch.Tensor, seq_len: torch.Tensor, tenant_id: torch.Tensor,
                  Wr: torch.Tensor, pool: str = "mean", act: str = "identity",
                  route_out: Optional[torch.Tensor] = None, want_logits: bool = True,
-                 workspace: Optional[torch.Tensor] = None):
-    """Prompt-aware router of one layer; returns (route uint8 [B], logits float32 [B,7] or None)."""
+                 workspace: Optional[torch.Tensor] = None, w_sa: Optional[torch.Tensor] = None,
+                 act_coef: Optional[Sequence[float]] = None):
+    """Prompt-aware router of one layer; returns (route uint8 [B], logits float32 [B,7] or None).
+
+    pool "selfattn" needs w_sa [T, d]; act "rational" needs the 12 coefficients a_0..a_6, b_1..b_5."""
     M_tok, d = H.shape
     B = tenant_id.numel()
     T = Wr.shape[0]
@@ -193,9 +197,16 @@ def milora_route(H: torch.Tensor, seq_start: torch.Tensor, seq_len: torch.Tensor
     logits = torch.empty(B, NUM_SITES, dtype=torch.float32, device=H.device) if want_logits else None
     if workspace is None:
         workspace = _workspace(route_workspace_bytes(B, d, M_tok), H.device)
+    if w_sa is not None and (w_sa.shape != (T, d) or w_sa.dtype != H.dtype):
+        raise ValueError("w_sa must be [T, d] in the dtype of H")
+    coef = None
+    if act_coef is not None:
+        if len(act_coef) != 12:
+            raise ValueError("act_coef holds a_0..a_6 and b_1..b_5")
+        coef = (ctypes.c_float * 12)(*[float(c) for c in act_coef])
     rc = lib().milora_route(_dev(H), M_tok, d, _dtype_code(H), _dev(seq_start, torch.int32),
                             _dev(seq_len, torch.int32), _dev(tenant_id, torch.int32), B, T, _dev(Wr), POOL[pool],
-                            ACT[act], _dev(route_out, torch.uint8), _dev(logits), _dev(workspace),
+                            ACT[act], _dev(w_sa), coef, _dev(route_out, torch.uint8), _dev(logits), _dev(workspace),
                             workspace.numel(), _stream())
     if rc != 0:
         raise MiloraError(rc, "milora_route")

@@ -13,7 +13,7 @@ import torch
 import oracle
 from paper_2410_18035_amd import binding as mb
 from paper_2410_18035_amd import synth
-from tests.util import (TOL, assert_routes_match, assert_rows_close, oracle_adapters, to_f64)
+from tests.util import (TOL, assert_routes_match, assert_rows_close, oracle_adapters, row_rel_err, to_f64)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -68,6 +68,48 @@ def test_route_ragged(dtype, pool, act, d):
     # same prompt, same table: the router is deterministic
     route2, _ = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, pool, act)
     assert torch.equal(route, route2)
+
+
+RATIONAL_COEF = [0.1, 1.0, 0.3, -0.2, 0.05, 0.01, -0.003, 0.5, -0.25, 0.1, 0.02, -0.01]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pool,act", [("max", "identity"), ("max", "gelu"), ("selfattn", "identity"),
+                                      ("selfattn", "rational"), ("mean", "rational"), ("last", "rational")])
+@pytest.mark.parametrize("d", [256, 100, 1032])
+def test_route_more_poolers_and_the_rational_activation(dtype, pool, act, d):
+    """Max and self-attention pooling (App. C) and the rational activation (Sec. 3.4) on ragged prompts from one
+    token to more than one 256-token block per slice."""
+    wl = small(dtype=dtype, d=d, T=6, B=19, prompt_len=(1, 300), pool="mean", tenants="uniform", seed=d + 1)
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    sl[0] = 1
+    Wr = synth.router_weights(wl, 0, DEV)
+    w_sa = synth.selfattn_query(wl, 0, DEV) * 8 if pool == "selfattn" else None  # scores of a few units: a peaked softmax
+    coef = RATIONAL_COEF if act == "rational" else None
+    tid = synth.tenant_ids(wl).to(DEV)
+    route, logits = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, pool, act, w_sa=w_sa, act_coef=coef)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[pool], mb.ACT[act],
+                       w_sa=None if w_sa is None else np_of(w_sa), act_coef=coef)
+    excluded = assert_routes_match(route, ref, wl.torch_dtype)
+    assert excluded <= 0.11
+    np.testing.assert_allclose(to_f64(logits), ref.logits, atol=2e-5 * max(1.0, np.abs(ref.logits).max()))
+    route2, _ = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, pool, act, w_sa=w_sa, act_coef=coef)
+    assert torch.equal(route, route2)
+
+
+def test_route_self_attention_long_prompts_full_width():
+    """d = 4096 bf16, prompts of up to 5000 tokens: several 256-token blocks per slice, rescaling of the running sums."""
+    wl = small(dtype="bf16", d=4096, T=3, B=5, prompt_len=(2000, 5000), tenants="uniform", seed=77)
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    w_sa = synth.selfattn_query(wl, 0, DEV) * 4
+    tid = synth.tenant_ids(wl).to(DEV)
+    for pool in ("selfattn", "max"):
+        route, logits = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, pool, "tanh", w_sa=w_sa)
+        ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[pool], oracle.ACT_TANH,
+                           w_sa=np_of(w_sa))
+        assert_routes_match(route, ref, torch.bfloat16, pool)
+        np.testing.assert_allclose(to_f64(logits), ref.logits, atol=1e-4 * max(1.0, np.abs(ref.logits).max()))
 
 
 def test_route_padded_prompts_and_bad_requests():
@@ -427,6 +469,76 @@ def test_headline_shape_one_step_full_parity():
     assert excluded <= 0.1
     worst = _layer_case(wl, False, mb.W_PACKED, steps=1, route=torch.from_numpy(ref.route.copy()))
     print(f"7B layer: excluded routes {excluded:.3f}, worst row rel err {worst:.3e}")
+
+
+# ------------------------------------------------------------------------------------------- layer stacks
+def _bf16_bits(y64):
+    """fp64 -> the bf16 the method would store between layers, as the oracle's input bit pattern."""
+    return np_of(torch.from_numpy(np.ascontiguousarray(y64)).to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("cfg,sample", [("llama7b_stack_b64", (0, 17, 42, 63)), ("llama13b_stack_b128", (3, 64, 127))])
+def test_decode_stack_sampled_requests(cfg, sample):
+    """The 32- and 40-layer stacks at their real shapes and batch sizes, layer after layer (weights of one layer
+    at a time), two decode steps.  The GPU runs all requests; the oracle follows a sample of them through the whole
+    chain on its own (requests are independent rows: the RMS norm is per row), rounding to bf16 between layers
+    as the method stores activations.  Two comparisons:
+    * every layer, with the sampled rows of the GPU's input replaced by the oracle chain's state (same stored
+      input on both sides): the per-call tolerance 2e-2;
+    * the GPU's own chain against the oracle's after the first layer, half way and at the end: the two chains
+      round at different places (the GPU keeps v, n(h), m in bf16 between the linears of a layer, the oracle
+      nothing), per-layer differences are independent and the layer map has slope ~1 under the RMS norm, so they
+      add in quadrature: 2e-2 * sqrt(layers so far)."""
+    wl = synth.CONFIGS[cfg]
+    sample = list(sample)
+    tid = synth.tenant_ids(wl)
+    table = synth.constructed_routes(wl)  # [L][B]: the table is an input of decode
+    tid_s = torch.arange(len(sample), dtype=torch.int32)
+    steps = 2
+    xs = [synth.decode_input(wl, s, DEV) for s in range(steps)]  # the GPU's own chain
+    xr = [np_of(x[sample]) for x in xs]                          # the oracle's chain (bf16 bit patterns)
+    ws = torch.zeros(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, max(wl.ranks)), dtype=torch.uint8, device=DEV)
+    worst_same, worst_free = 0.0, 0.0
+    for layer in range(wl.L):
+        W, ad, tab = device_layer(wl, layer)
+        Wp = [mb.milora_pack_weight(w) for w in W]
+        Wn = [np_of(w) for w in W]
+        sub = [int(tid[b]) for b in sample]
+        adn = oracle.Adapters([[np_of(a) for a in ad.A[t]] for t in sub], [[np_of(b) for b in ad.B[t]] for t in sub],
+                              [ad.rank[t] for t in sub])
+        route = table[layer]
+        for s in range(steps):
+            x_same = xs[s].clone()
+            x_same[sample] = torch.from_numpy(xr[s].view(np.int16)).view(torch.bfloat16).to(DEV)
+            y_same, _ = mb.milora_layer_decode(x_same, Wp, tab, tid.to(DEV), route.to(DEV), wl.F, w_layout=mb.W_PACKED,
+                                               rmsnorm=wl.rmsnorm, workspace=ws)
+            y, _ = mb.milora_layer_decode(xs[s], Wp, tab, tid.to(DEV), route.to(DEV), wl.F, w_layout=mb.W_PACKED,
+                                          rmsnorm=wl.rmsnorm, workspace=ws)
+            y_ref, _ = oracle.layer_decode(xr[s], Wn, adn, tid_s.numpy(), route[sample].numpy(), wl.F,
+                                           flags=oracle.FLAG_RMSNORM if wl.rmsnorm else 0)
+            worst_same = max(worst_same, assert_rows_close(y_same[sample], y_ref, torch.bfloat16,
+                                                           f"{cfg} layer {layer} step {s}, same input"))
+            if layer in (0, wl.L // 2, wl.L - 1):
+                err = row_rel_err(to_f64(y[sample]), y_ref).max()
+                bound = TOL[torch.bfloat16] * np.sqrt(layer + 1)
+                assert err <= bound, f"{cfg} layer {layer} step {s}: chains differ by {err:.3e} > {bound:.3e}"
+                worst_free = max(worst_free, float(err))
+            xs[s], xr[s] = y, _bf16_bits(y_ref)
+        del W, Wp, ad, tab
+    print(f"{cfg}: worst row error with the same input {worst_same:.2e}, between the free-running chains {worst_free:.2e}")
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_route_stack_config_ragged_prompts(layer):
+    """Router at the 32-layer configuration's shape: 64 prompts of 128..1024 tokens, tenants drawn with replacement."""
+    wl = synth.CONFIGS["llama7b_stack_b64"]
+    H, ss, sl = synth.prompts(wl, layer, DEV)
+    Wr = synth.router_weights(wl, layer, DEV)
+    tid = synth.tenant_ids(wl)
+    route, logits = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid.to(DEV), Wr, wl.pool, wl.act)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.numpy(), np_of(Wr), mb.POOL[wl.pool], mb.ACT[wl.act])
+    assert_routes_match(route, ref, torch.bfloat16, f"layer {layer}")
+    np.testing.assert_allclose(to_f64(logits), ref.logits, rtol=0, atol=2e-2 * np.abs(ref.logits).max())
 
 
 # ------------------------------------------------------------------------------------------- error paths
