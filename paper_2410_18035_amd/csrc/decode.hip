@@ -31,11 +31,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) u32x4 gu32x4;  // in global memory: loads count on the vector-memory counter only
+typedef __attribute__((address_space(1))) u32x2 gu32x2;
+typedef __attribute__((address_space(1))) bf16_t gbf16;  // adapter matrices are reached through pointer tables read at run time
 
 namespace {
 
 constexpr int kSW = 6;                  // stream waves per workgroup
-constexpr int kLoader = kSW;            // wave index of the input loader
+constexpr int kLoaders = 1;             // waves that copy the stage input (the LoRA wave is the second one)
+constexpr int kLoader = kSW;            // wave index of the (first) input loader
 constexpr int kLora = kSW + 1;          // wave index of the LoRA wave
 constexpr int kWaves = kSW + 2;
 constexpr int kThreads = kWaves * 64;
@@ -85,7 +88,9 @@ struct Params {
   const int32_t* row_to_req;
   int lora;
   float* tpart;   // [M][nc_max][r_max] shrink partials t = x[chunk] . A[chunk]
-  int* pready;    // [M][nc_max] epoch of the launch that wrote the partial
+  float* tfin;    // [M][r_max] t = x . A: the partials summed in chunk order by the wave that wrote the last one
+  int* tcount;    // [M] partials of the row written so far in this launch; zero between launches
+  int* tready;    // [M] epoch of the launch whose t is in tfin
   int nc_max;
   int* flags;     // [kMaxGrid] grid barrier flags, monotone
   int* status;    // set to 1 when a bounded wait ran out
@@ -97,7 +102,7 @@ struct Ctrl {
   int tb_seg[kMaxStages][8];
   int tb_tile[kMaxStages][8];
   int ns[kMaxStages];
-  int x_ready;
+  int x_ready[2];  // per loader wave: chunks it has landed, counted over all stages
   int x_done[8];
   int slot_turn[8];  // per partial-tile area: stream waves that have put their tiles in, counted over all stages
   int part_cnt;      // the same over all areas
@@ -218,7 +223,7 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
   int tenant = 0;
   const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, site, &tenant);
   if (r == 0) return;
-  const bf16_t* A = (const bf16_t*)p.ad.A[tenant * MILORA_NUM_SITES + site];
+  const gbf16* A = (const gbf16*)p.ad.A[tenant * MILORA_NUM_SITES + site];
   const int K = sg.K, rmax = p.ad.r_max;
   const int k_lo = kc * kShrinkChunk;
   const int k_hi = k_lo + kShrinkChunk < K ? k_lo + kShrinkChunk : K;
@@ -237,7 +242,7 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
     float acc[8];
 #pragma unroll
     for (int v = 0; v < 8; ++v) acc[v] = 0.f;
-    const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + cg;
+    const gu32x4* Ap = reinterpret_cast<const gu32x4*>(A) + cg;
     int k = k_lo + kr;
     for (; k + 31 * kpl < k_hi; k += 32 * kpl) {  // rank 32: the whole chunk in one round trip
       u32x4 a[32];
@@ -278,9 +283,31 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
       st_agent(out + c, acc);
     }
   }
-  // publish the partial: readers sum a row's partials themselves, in chunk order
+  // The wave that completes the row's last partial adds all of them in chunk order (whoever it is: the order
+  // of the sum is fixed) and publishes t; every workgroup with a tile of the site reads it from there.
   wait_all_mem();
-  if (lane == 0) st_agent(&p.pready[m * p.nc_max + kc], epoch);
+  int done = 0;
+  if (lane == 0) done = __hip_atomic_fetch_add(&p.tcount[m], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+  done = __builtin_amdgcn_readfirstlane(done);
+  if (done == NC) {
+    for (int c = lane; c < r; c += 64) {
+      const float* tp = row_part + c;
+      float t = 0.f;
+      for (int k0 = 0; k0 < NC; k0 += 8) {  // eight loads in flight, added in chunk order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = ld_agent(tp + (size_t)(k0 + u < NC ? k0 + u : NC - 1) * rmax);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t += k0 + u < NC ? v[u] : 0.f;
+      }
+      st_agent(p.tfin + (size_t)m * rmax + c, t);
+    }
+    wait_all_mem();
+    if (lane == 0) {
+      st_agent(&p.tcount[m], 0);
+      st_agent(&p.tready[m], epoch);
+    }
+  }
 }
 
 template <int MT>
@@ -344,7 +371,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     }
   }
   if (tid == 0) {
-    c.x_ready = 0;
+    c.x_ready[0] = 0;
+    c.x_ready[1] = 0;
     c.part_cnt = 0;
     c.sum_cnt = 0;
     c.red_free = 0;
@@ -442,7 +470,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     }
     prod_round_end();
 
-    int nseq = 0;  // input chunks of the earlier stages
+    int nseq = 0;            // input chunks of the earlier stages
+    int lbase[2] = {0, 0};   // ... and how many of them each loader wave brought
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
       const int K = sg.K, KT = K >> 5;
@@ -466,7 +495,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         static_assert(D % NSMAX == 0, "ring rounds must hold whole k blocks");
         u32x4 xb[MT], xn[MT];  // operand blocks of the current k block and, when it was there in time, the next one
         bool have_next = false;
-        int seen = 0;          // input chunks known to have landed (a cached copy of the loader's counter)
+        int seen[2] = {0, 0};  // input chunks known to have landed (cached copies of the loaders' counters)
         const bool norm = sg.norm != 0;
         // this lane's (row lane % 16, k group lane / 16) inside an input block: packed blocks hold it at slot
         // lane, gathered row-major blocks at slot row * 4 + k group
@@ -483,8 +512,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
                 compiler_fence();
                 st_lds(&c.x_done[w], nseq + i);
                 if (!have_next) {
-                  if (seen <= nseq + i) {
-                    spin_until([&]() { return (seen = ld_lds(&c.x_ready)) > nseq + i; });
+                  if (seen[i % kLoaders] <= lbase[i % kLoaders] + i / kLoaders) {
+                    spin_until([&]() { return (seen[i % kLoaders] = ld_lds(&c.x_ready[i % kLoaders])) > lbase[i % kLoaders] + i / kLoaders; });
                   }
                   const unsigned char* xbuf = xreg + (i % NBUF) * kChunkBytes;
 #pragma unroll
@@ -495,7 +524,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
                   for (int mt = 0; mt < MT; ++mt) xb[mt] = xn[mt];
                 }
                 // the chunk after it, if the loader is that far: its LDS reads overlap this k block's work
-                have_next = i + 1 < NCH && seen > nseq + i + 1;
+                have_next = i + 1 < NCH && seen[(i + 1) % kLoaders] > lbase[(i + 1) % kLoaders] + (i + 1) / kLoaders;
                 if (have_next) {
                   const unsigned char* xbuf = xreg + ((i + 1) % NBUF) * kChunkBytes;
 #pragma unroll
@@ -543,6 +572,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       compiler_fence();
       st_lds(&c.x_done[w], nseq + NCH);
       nseq += NCH;
+      lbase[0] += (NCH + kLoaders - 1) / kLoaders;
+      lbase[1] += kLoaders > 1 ? NCH / kLoaders : 0;
 
       // ---- stage end: the waves' partial tiles meet in LDS ------------------------------------------------
       // Wave w puts its partial tiles into slot w / CHAIN (the first wave of a slot stores, the others add in
@@ -604,18 +635,10 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     return ((a * MT + (m >> 4)) * 4 + (nl & 3)) * 64 + (m & 15) + 16 * (nl >> 2);
   };
   // LoRA expand of list entries [l0, l1): lane = (entry, tile, column quad); added to `red` or stored in `delta`
-  // shrink t[c] of row m: the chunk partials summed in chunk order
+  // shrink t[c] of row m, as published by the wave that summed the row's partials
   auto t_sum = [&](int m, int c, int NC) __attribute__((always_inline)) -> float {
-    const float* tp = p.tpart + ((size_t)m * p.nc_max) * p.ad.r_max + c;
-    float t = 0.f;
-    for (int k0 = 0; k0 < NC; k0 += 8) {  // eight loads in flight, added in chunk order
-      float v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = ld_agent(tp + (size_t)(k0 + u < NC ? k0 + u : NC - 1) * p.ad.r_max);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) t += k0 + u < NC ? v[u] : 0.f;
-    }
-    return t;
+    (void)NC;
+    return ld_agent(p.tfin + (size_t)m * p.ad.r_max + c);
   };
   auto expand = [&](const int L, const Stage& sg, const int NS, const int NC, int l0, int l1, bool to_red) __attribute__((always_inline)) {
     const int work = (l1 - l0) * NS * 4;
@@ -629,7 +652,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         const int r = c.l_r[li];
         const int n = c.tb_tile[L][a] * 16 + q * 4;
         const size_t ldb = (size_t)sg.N[s];
-        const bf16_t* Bm = (const bf16_t*)p.ad.B[c.l_t[li] * MILORA_NUM_SITES + sg.site[s]] + n;
+        const gbf16* Bm = (const gbf16*)p.ad.B[c.l_t[li] * MILORA_NUM_SITES + sg.site[s]] + n;
         const float* tv = t_lds + (size_t)li * p.ad.r_max;  // entries formed ahead of the stage end have t in LDS
         if (((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0) {
           int cc = 0;
@@ -638,7 +661,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             float t[16];
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
-              bb[u] = *reinterpret_cast<const u32x2*>(Bm + (size_t)(cc + u) * ldb);
+              bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(cc + u) * ldb);
               t[u] = to_red ? t_sum(m, cc + u, NC) : tv[cc + u];
             }
 #pragma unroll
@@ -650,7 +673,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             }
           }
           for (; cc < r; ++cc) {
-            const u32x2 bb = *reinterpret_cast<const u32x2*>(Bm + (size_t)cc * ldb);
+            const u32x2 bb = *reinterpret_cast<const gu32x2*>(Bm + (size_t)cc * ldb);
             const float t = to_red ? t_sum(m, cc, NC) : tv[cc];
             d[0] += t * __uint_as_float(bb[0] << 16);
             d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
@@ -731,19 +754,11 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     }
   };
 
-  int nseq = 0;  // input chunks of the earlier stages
-  if (w == kLoader) {
-    // ===================================== input loader =====================================
-    for (int L = 0; L < p.n_stages; ++L) {
-      const Stage& sg = p.st[L];
-      const int K = sg.K, KT = K >> 5;
-      const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
-      const int NCH = chunks_of(NS, KT);
-      const int NBUF = nbuf_of(NS);
-      if (sg.sync_before && L > 0) {
-        if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
-      }
-      if (NS > 0) {
+  // ---- input copies of one stage by loader wave `lj` of kLoaders (it takes every kLoaders-th chunk) ------------
+  int lcount = 0;  // chunks this wave has brought in the earlier stages
+  auto load_input = [&](const int L, const Stage& sg, const int KT, const int NS, const int NCH, const int NBUF,
+                        const int nseq, const int lj) __attribute__((always_inline)) {
+    if (NS > 0) {
         // A block is the 1 KiB operand of one k block and one 16-row tile; lane l of the consumer holds
         // (row l % 16, k group l / 16).  The copies go from global memory straight into LDS (lane l of a wave load
         // lands at base + 16 l) and take no registers, so many chunks can be in flight; a chunk is announced once
@@ -765,13 +780,13 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         }
         const size_t kstep = xpk ? (size_t)MT * 1024 : 64;  // bytes from one k block to the next
         const int rot = start_of(NCH);
-        const uint32_t done_off = lds_off(&c.x_done[lane < kSW ? lane : 0]), ready_off = lds_off(&c.x_ready);
+        const uint32_t done_off = lds_off(&c.x_done[lane < kSW ? lane : 0]), ready_off = lds_off(&c.x_ready[lj]);
         const uint32_t sum_off = lds_off(&c.sum_cnt);
         // the chunk buffers may overlap the previous stage's slots: all of its partial tiles have been summed
         spin_until([&]() { return lds_peek(sum_off) >= L * kSW; });
-        const int depth = kDepth < NBUF ? kDepth : NBUF;  // chunks in flight
-        int published = 0, done_seen = 0;
-        for (int ch = 0; ch < NCH; ++ch) {
+        const int depth = kDepth * kLoaders <= NBUF ? kDepth : (NBUF / kLoaders > 0 ? NBUF / kLoaders : 1);  // own chunks in flight
+        int done_seen = 0, mine = 0;  // own chunks issued
+        for (int ch = lj; ch < NCH; ch += kLoaders, ++mine) {
           // the buffer's previous chunk (of this stage, or any chunk of an earlier stage) has been consumed by
           // every stream wave
           const int need = nseq + (ch >= NBUF ? ch - NBUF + 1 : 0);
@@ -802,16 +817,31 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
                                                (__attribute__((address_space(3))) void*)(dst + ((pos * MT + mt) << 10)), 16, 0, 0);
           }
           // with `depth` chunks in flight the oldest has landed once at most (depth - 1) chunks of loads are out
-          if (ch + 1 >= depth) {
+          if (mine + 1 >= depth) {
             if (depth == kDepth) wait_vm<LPC * (kDepth - 1)>();
             else wait_vm<0>();
-            published = depth == kDepth ? ch + 2 - depth : ch + 1;
-            lds_poke(ready_off, nseq + published);
+            lds_poke(ready_off, lcount + (depth == kDepth ? mine + 2 - depth : mine + 1));
           }
         }
         wait_vm<0>();
-        lds_poke(ready_off, nseq + NCH);
+        lcount += mine;
+        lds_poke(ready_off, lcount);
       }
+  };
+
+  int nseq = 0;  // input chunks of the earlier stages
+  if (w == kLoader) {
+    // ===================================== input loader =====================================
+    for (int L = 0; L < p.n_stages; ++L) {
+      const Stage& sg = p.st[L];
+      const int K = sg.K, KT = K >> 5;
+      const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
+      const int NCH = chunks_of(NS, KT);
+      const int NBUF = nbuf_of(NS);
+      if (sg.sync_before && L > 0) {
+        if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
+      }
+      load_input(L, sg, KT, NS, NCH, NBUF, nseq, 0);
       nseq += NCH;
       // ---- stage end: the LoRA wave has added the LoRA terms to the sums ---------------------------------------
       spin_until([&]() { return ld_lds(&c.tail_go) >= L + 1; });
@@ -833,6 +863,14 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         const int items = p.M * NC;
         // spread the items of consecutive rows over the grid, and of consecutive stages over different workgroups
         for (int it = (wg + 97 * L) % G; it < items; it += G) lora_shrink_item<MT>(p, sg, it / NC, it % NC, NC, epoch, lane);
+      }
+      if (kLoaders > 1) {
+        const int KT = K >> 5;
+        if (sg.sync_before && L > 0 && !(p.lora && sg.lora_shrink)) {
+          if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
+        }
+        load_input(L, sg, KT, NS, chunks_of(NS, KT), nbuf_of(NS), nseq, 1);
+        nseq += chunks_of(NS, KT);
       }
       // ---- rows whose LoRA term lands in this workgroup's tiles; their expand is formed ahead of the stage end ----
       int cnt = 0, npre = 0;
@@ -858,12 +896,12 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         }
         wave_sync();
         cnt = __builtin_amdgcn_readfirstlane(c.l_cnt);
-        // every shrink partial of these rows has been written: lane = (entry, chunk)
+        // the shrinks of these rows have been published: lane = entry
         {
           int spins = 0;
-          for (int e = lane; e < ((cnt * NC + 63) & ~63); e += 64) {
-            const int* f = p.pready + c.l_m[e < cnt * NC ? e / NC : 0] * p.nc_max + (e < cnt * NC ? e % NC : 0);
-            while (!__all(e >= cnt * NC || ld_agent(f) == epoch)) {
+          for (int e = lane; e < ((cnt + 63) & ~63); e += 64) {
+            const int* f = p.tready + c.l_m[e < cnt ? e : 0];
+            while (!__all(e >= cnt || ld_agent(f) == epoch)) {
               if (++spins >= kSpinLimit) { *p.status = 1; break; }
               __builtin_amdgcn_s_sleep(2);
             }
@@ -1026,8 +1064,10 @@ bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_ma
 struct DecodeWs {
   int* flags;      // [kMaxGrid] barrier flags; zero before the first launch, then owned by the kernels
   int* status;
-  int* pready;     // [M][NCmax] epochs of the shrink partials
-  float* tpart;    // [M][NCmax][r_max]
+  int* tready;     // [M] epoch of the launch that published the row's shrink
+  int* tcount;     // [M] partials written so far (zero between launches)
+  float* tfin;     // [M][r_max] published shrinks
+  float* tpart;    // [M][NCmax][r_max] shrink partials
   float* h_f32;    // [M][d]
   bf16_t* v_pk;    // a = v as operand blocks   (K = d)
   bf16_t* h_pk;    // h as operand blocks       (K = d)
@@ -1040,7 +1080,8 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
   size_t off = 0;
   auto take = [&](size_t n) { size_t o = off; off += align_up(n, 256); return o; };
   const size_t o_fl = take((size_t)(kMaxGrid + 64) * sizeof(int));
-  const size_t o_p = take((size_t)M * shrink_chunks(big) * sizeof(int));
+  const size_t o_p = take((size_t)kMaxRows * 2 * sizeof(int));  // at a fixed place whatever M is: the counters must read zero
+  const size_t o_tf = take((size_t)M * r_max * sizeof(float));
   const size_t o_t = take((size_t)M * shrink_chunks(big) * r_max * sizeof(float));
   const size_t o_h = take((size_t)M * d * sizeof(float));
   const int rows = mt_for(M) * 16;
@@ -1049,15 +1090,15 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
   const size_t o_m = take((size_t)rows * F * sizeof(bf16_t));
   char* b = (char*)base;
   int* fl = (int*)(b + o_fl);
-  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (float*)(b + o_t), (float*)(b + o_h), (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb),
-                  (bf16_t*)(b + o_m), off};
+  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (int*)(b + o_p) + kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
+                  (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb), (bf16_t*)(b + o_m), off};
 }
 
 void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const AdapterView& ad, const int32_t* tenant_id,
                  const uint8_t* route, const int32_t* row_to_req) {
   p.n_stages = 0; p.M = M; p.Breq = Breq; p.ad = ad; p.tenant_id = tenant_id; p.route = route; p.row_to_req = row_to_req;
   p.lora = 1;
-  p.tpart = ws.tpart; p.pready = ws.pready; p.nc_max = shrink_chunks(Kmax);
+  p.tpart = ws.tpart; p.tfin = ws.tfin; p.tcount = ws.tcount; p.tready = ws.tready; p.nc_max = shrink_chunks(Kmax);
   p.flags = ws.flags; p.status = ws.status;
 }
 
