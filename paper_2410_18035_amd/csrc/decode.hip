@@ -705,8 +705,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     for (int e = half * 64 + lane; e < work; e += 128) {
       const int hf = e & 1, m = (e >> 1) % p.M, ao = (e >> 1) / p.M;
       const int a = sg.pair ? 2 * ao : ao;
+      if (c.tb_seg[L][a] < 0) continue;  // filler tile: streamed to keep the ring rounds whole, result dropped
       const int s = sg.pair ? 0 : c.tb_seg[L][a];
-      if (s < 0) continue;
       const int n = c.tb_tile[L][a] * 16 + hf * 8;
       const float inv = c.inv_rows[m];
       float val[8];

@@ -420,6 +420,13 @@ def test_layer_decode_packed_long_ragged_reduction(B):
     _layer_case(wl, True, mb.W_PACKED)
 
 
+def test_layer_decode_packed_gate_up_tile_pairs_do_not_fill_the_last_workgroup():
+    """F / 16 = 692 gate/up tile pairs over 256 workgroups of 3: the last one with work holds 2 pairs and streams a
+    filler pair to keep its rounds whole; the filler's result must be dropped."""
+    wl = small(dtype="bf16", d=64, F=11072, T=3, B=4, ranks=(8,), tenants="uniform", seed=91)
+    assert _layer_case(wl, False, mb.W_PACKED) <= TOL[torch.bfloat16]
+
+
 def test_layer_decode_packed_reuses_buffers_across_steps():
     # the serving pattern: one zero-filled workspace and one set of output buffers, many launches with fresh
     # inputs; every step is checked (a stale hand-over flag or a stale cached activation would show up here)
