@@ -32,7 +32,7 @@ constexpr int kHalfBytes = (kBlocksM + kBlocksN) / 2 * kBlockBytes;  // 8 X bloc
 constexpr int kHalves = 5;                                // ring of half steps
 constexpr int kLdsBytesP = kHalves * kHalfBytes;
 constexpr int kAccTilesRows = 6;
-constexpr int kGroupM = 8;  // consecutive workgroups of an XCD walk 8 row tiles of one column tile
+constexpr int kGroupM = 4;  // consecutive workgroups of an XCD walk 4 row tiles of one column tile
 
 struct PParams {
   const bf16_t* X;
@@ -89,6 +89,7 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
 
   // workgroup -> tile: workgroup ids go round-robin over the 8 XCDs; each XCD takes a contiguous run of the
   // tile order, which walks kGroupM row tiles per column tile so that the XCD's L2 serves the re-reads
+  // (the 32 workgroups resident on an XCD then cover 4 row tiles x 8 column tiles)
   const int total = p.tilesM * p.tilesN;
   const int per = (total + 7) / 8;
   const int id = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
