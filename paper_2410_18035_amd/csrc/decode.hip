@@ -116,6 +116,10 @@ struct Ctrl {
   float ss_part[kSW][kMaxRows];
   float inv_rows[kMaxRows];
   int l_m[kMaxRows], l_r[kMaxRows], l_t[kMaxRows], l_s[kMaxRows];
+  // what the route table says about each row, looked up once per launch: site (-1: no LoRA term), tenant, rank
+  int r_site[kMaxRows], r_ten[kMaxRows], r_rank[kMaxRows];
+  int s_rows[kMaxRows];  // rows with a shrink in the current level
+  int s_cnt;
 };
 static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
 
@@ -211,18 +215,8 @@ __device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, i
 
 // ---- one LoRA shrink item by one wave: partial t of row m over one k chunk ---------------------------
 template <int MT>
-__device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& sg, int m, int kc, int NC, int epoch,
-                                                 int lane) {
-  const int req = p.row_to_req ? p.row_to_req[m] : m;
-  if (req < 0 || req >= p.Breq) return;
-  const int site = p.route[req];
-  int slot = -1;
-  for (int s = 0; s < sg.n_seg; ++s)
-    if (sg.site[s] == site) slot = s;
-  if (slot < 0) return;
-  int tenant = 0;
-  const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, site, &tenant);
-  if (r == 0) return;
+__device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& sg, int m, int site, int tenant, int r,
+                                                 int kc, int NC, int epoch, int lane) {
   const gbf16* A = (const gbf16*)p.ad.A[tenant * MILORA_NUM_SITES + site];
   const int K = sg.K, rmax = p.ad.r_max;
   const int k_lo = kc * kShrinkChunk;
@@ -383,6 +377,23 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   if (tid < 8) {
     c.x_done[tid] = 0;
     c.slot_turn[tid] = 0;
+  }
+  if (tid >= 64 && tid < 64 + kMaxRows) {
+    const int m = tid - 64;
+    int site = -1, tenant = 0, r = 0;
+    if (m < p.M && p.lora) {
+      const int req = p.row_to_req ? p.row_to_req[m] : m;
+      if (req >= 0 && req < p.Breq) {
+        const int st = p.route[req];
+        if (st < MILORA_NUM_SITES) {
+          r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, st, &tenant);
+          if (r > 0) site = st;
+        }
+      }
+    }
+    c.r_site[m] = site;
+    c.r_ten[m] = tenant;
+    c.r_rank[m] = r;
   }
   __syncthreads();
   const int epoch = __builtin_amdgcn_readfirstlane(c.epoch);
@@ -860,9 +871,29 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         if (sg.sync_before && L > 0) {
           if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
         }
-        const int items = p.M * NC;
+        // the rows with a LoRA term at one of this level's sites, in row order (the same list in every workgroup)
+        if (lane == 0) c.s_cnt = 0;
+        wave_sync();
+        for (int m0 = 0; m0 < p.M; m0 += 64) {
+          const int m = m0 + lane;
+          bool has = false;
+          if (m < p.M) {
+            const int st = c.r_site[m];
+            for (int s = 0; s < sg.n_seg; ++s) has = has || (st >= 0 && sg.site[s] == st);
+          }
+          const unsigned long long mask = __ballot(has);
+          const int base = c.s_cnt;
+          if (has) c.s_rows[base + __popcll(mask & ((1ull << lane) - 1ull))] = m;
+          wave_sync();
+          if (lane == 0) c.s_cnt = base + __popcll(mask);
+          wave_sync();
+        }
+        const int items = c.s_cnt * NC;
         // spread the items of consecutive rows over the grid, and of consecutive stages over different workgroups
-        for (int it = (wg + 97 * L) % G; it < items; it += G) lora_shrink_item<MT>(p, sg, it / NC, it % NC, NC, epoch, lane);
+        for (int it = (wg + 97 * L) % G; it < items; it += G) {
+          const int m = c.s_rows[it / NC];
+          lora_shrink_item<MT>(p, sg, m, c.r_site[m], c.r_ten[m], c.r_rank[m], it % NC, NC, epoch, lane);
+        }
       }
       if (kLoaders > 1) {
         const int KT = K >> 5;
@@ -878,19 +909,15 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         if (lane == 0) c.l_cnt = 0;
         wave_sync();
         for (int m = lane; m < p.M; m += 64) {
-          const int req = p.row_to_req ? p.row_to_req[m] : m;
-          if (req >= 0 && req < p.Breq) {
-            const int site = p.route[req];
+          const int site = c.r_site[m];
+          if (site >= 0) {
             for (int s = 0; s < sg.n_seg; ++s) {
               if (sg.site[s] != site) continue;
-              int tenant = 0;
-              const int r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, site, &tenant);
-              if (r == 0) continue;
               bool mine = false;  // does the workgroup hold a tile of this site?
               for (int a = 0; a < NS; ++a) mine = mine || c.tb_seg[L][a] == s;
               if (!mine) continue;
               const int idx = atomicAdd(&c.l_cnt, 1);
-              c.l_m[idx] = m; c.l_r[idx] = r; c.l_t[idx] = tenant; c.l_s[idx] = s;
+              c.l_m[idx] = m; c.l_r[idx] = c.r_rank[m]; c.l_t[idx] = c.r_ten[m]; c.l_s[idx] = s;
             }
           }
         }
