@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, vendor figure
 # by what the counter reads for a plain 1 GiB device copy (profiles/decode_layer_llama7b_b32_hbm_counters.txt).
 # Valid only for the kernel source the counters were taken on: keyed by workload and source digest.
 MEASURED_TRAFFIC = {
-    ("llama7b_layer_b32", "5f8141b2119d47e9"): {"fetch_bytes": 506058752, "write_bytes": 3688243},
+    ("llama7b_layer_b32", "6b06449dfa5e85e6"): {"fetch_bytes": 504586953, "write_bytes": 3694336},
 }
 
 

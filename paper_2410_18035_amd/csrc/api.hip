@@ -211,7 +211,7 @@ extern "C" int milora_last_hip_error(void) { return g_last_hip_error; }
 
 extern "C" size_t milora_routed_linear_workspace_bytes(int64_t M, int d1, int d2, int r_max) {
   if (M < 1 || d1 < 1 || d2 < 1 || r_max < 1) return 0;
-  size_t generic = align_up((size_t)M * r_max * sizeof(float), 256);
+  size_t generic = align_up((size_t)M * r_max * sizeof(float) * kPrefillShrinkParts, 256);
   const int mp = M <= MILORA_MAX_DECODE_BATCH ? (int)M : MILORA_MAX_DECODE_BATCH;
   size_t packed = routed_linear_packed_workspace_bytes(mp, d1, d2, r_max);
   return generic > packed ? generic : packed;

@@ -99,6 +99,10 @@ struct LaunchMarks {
   int n;
 };
 
+// The many-row LoRA shrink cuts its reduction into this many parts (one workgroup each); the workspace holds
+// one [M][r_max] fp32 array per part.
+constexpr int kPrefillShrinkParts = 4;
+
 // ---- internal entry points shared between translation units ------------------------------------
 // LoRA shrink: for every row m whose request is routed to `site`, t[m][0..r) = X[m] . A (fp32).
 // t is [M][r_max] floats; rows that carry no LoRA term are left untouched.

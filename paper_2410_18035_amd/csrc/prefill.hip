@@ -32,6 +32,7 @@ constexpr int kHalfBytes = (kBlocksM + kBlocksN) / 2 * kBlockBytes;  // 8 X bloc
 constexpr int kHalves = 5;                                // ring of half steps
 constexpr int kLdsBytesP = kHalves * kHalfBytes;
 constexpr int kAccTilesRows = 6;
+constexpr int kShrinkSplit = kPrefillShrinkParts;  // the shrink's reduction is cut into this many parts, one workgroup each
 constexpr int kGroupM = 4;  // consecutive workgroups of an XCD walk 4 row tiles of one column tile
 
 struct PParams {
@@ -39,7 +40,8 @@ struct PParams {
   const bf16_t* W;
   const bf16_t* bias;
   bf16_t* Y;
-  const float* t;
+  const float* t;     // kShrinkSplit partial shrinks [part][rows of the whole call][r_max], to be added in part order
+  size_t t_stride;    // floats from one part to the next
   const int32_t* row_to_req;
   const int32_t* tenant_id;
   const uint8_t* route;
@@ -243,6 +245,34 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
     const uint32_t rb = (uint32_t)(tid & 15);
     const uint32_t blk = (uint32_t)(tid >> 7) * kHalfBytes + (uint32_t)((tid >> 4) & 7) * kBlockBytes + rb * 128;
     for (int c0 = 0; c0 < r; c0 += 32) {
+      // t of the tile's 256 rows for these 32 ranks, the shrink's parts added in part order, through LDS: eight
+      // lanes read the 128 bytes of a row (whole lines), then every thread picks up its own row
+      float* const ts = reinterpret_cast<float*>(lds + 2 * kHalfBytes + 1024);  // [256][33]
+      const bool vec = (p.ad.r_max & 3) == 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int row = (tid >> 3) + 32 * i, cq = c0 + (tid & 7) * 4;
+        const int64_t mr = m0 + row;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (mr < p.M) {
+          const float* q = p.t + (size_t)mr * p.ad.r_max + cq;
+          if (vec && cq + 3 < p.ad.r_max) {
+#pragma unroll
+            for (int part = 0; part < kShrinkSplit; ++part) {
+              const f32x4 x = *reinterpret_cast<const f32x4*>(q + part * p.t_stride);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] += x[e];
+            }
+          } else {
+            for (int e = 0; e < 4; ++e)
+              if (cq + e < p.ad.r_max)
+                for (int part = 0; part < kShrinkSplit; ++part) v[e] += q[part * p.t_stride + e];
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ts[row * 33 + (tid & 7) * 4 + e] = v[e];
+      }
+      __syncthreads();
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x4 hi, lo, wb;
@@ -253,7 +283,7 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
             const int c = c0 + g * 8 + e * 2 + h;
-            tv[h] = (my_ten == cur && c < r) ? p.t[(size_t)m * p.ad.r_max + c] : 0.f;
+            tv[h] = (my_ten == cur && c < r) ? ts[tid * 33 + (c - c0)] : 0.f;
             bw[h] = (c < r && n < p.d2) ? (uint32_t)Bm[(size_t)c * p.d2 + n] : 0u;
           }
           const bf16_t h0b = f32_to_bf16(tv[0]), h1b = f32_to_bf16(tv[1]);
@@ -311,7 +341,7 @@ __global__ void __launch_bounds__(256, 2) shrink_tiles_kernel(const bf16_t* __re
                                                               AdapterView ad, int site,
                                                               const int32_t* __restrict__ tenant_id,
                                                               const uint8_t* __restrict__ route, int B,
-                                                              float* __restrict__ t) {
+                                                              float* __restrict__ t, size_t t_stride) {
   __shared__ bf16_t As[kShrinkK][kShrinkLd];
   __shared__ int row_ten[kShrinkRows];
   __shared__ int next_ten;
@@ -328,6 +358,11 @@ __global__ void __launch_bounds__(256, 2) shrink_tiles_kernel(const bf16_t* __re
     row_ten[tid] = ten;
   }
   __syncthreads();
+  // this workgroup's part of the reduction (whole chunks; the last parts may be empty and then write zeros)
+  const int per_part = ((d1 + kShrinkSplit * kShrinkK - 1) / (kShrinkSplit * kShrinkK)) * kShrinkK;
+  const int k_begin = (int)blockIdx.y * per_part < d1 ? (int)blockIdx.y * per_part : d1;
+  const int k_end = k_begin + per_part < d1 ? k_begin + per_part : d1;
+  t += (size_t)blockIdx.y * t_stride;
   const int my_row = wave * 16 + (lane & 15);
   int64_t xrow = m0 + my_row;
   xrow = xrow < M ? xrow : M - 1;
@@ -352,8 +387,8 @@ __global__ void __launch_bounds__(256, 2) shrink_tiles_kernel(const bf16_t* __re
       // read a valid element instead (what they produce is never stored / never used)
       const int c = tid & 63;
       gbf16* ap = A + cb + (c < rc ? c : 0);
-      for (int k0 = 0; k0 < d1; k0 += kShrinkK) {
-        const int steps = d1 - k0 < kShrinkK ? (d1 - k0) / 32 : kShrinkK / 32;
+      for (int k0 = k_begin; k0 < k_end; k0 += kShrinkK) {
+        const int steps = k_end - k0 < kShrinkK ? (k_end - k0) / 32 : kShrinkK / 32;
         bf16x8 xf[kShrinkK / 32];
 #pragma unroll
         for (int ks = 0; ks < kShrinkK / 32; ++ks) xf[ks] = *(const bf16x8*)(xp + k0 + (ks < steps ? ks : 0) * 32);
@@ -361,7 +396,7 @@ __global__ void __launch_bounds__(256, 2) shrink_tiles_kernel(const bf16_t* __re
 #pragma unroll 16
         for (int i = 0; i < kShrinkK / 4; ++i) {
           int k = k0 + (tid >> 6) + 4 * i;
-          k = k < d1 ? k : d1 - 1;
+          k = k < k_end ? k : k_end - 1;
           As[(tid >> 6) + 4 * i][c] = ap[(size_t)k * r];
         }
         __syncthreads();
@@ -432,6 +467,7 @@ int routed_linear_prefill(const bf16_t* X, int64_t M, int d1, int d2, const int3
     p.bias = bias;
     p.Y = Y + (size_t)r0 * d2;
     p.t = t + (size_t)r0 * ad.r_max;
+    p.t_stride = (size_t)M * ad.r_max;
     p.row_to_req = row_to_req ? row_to_req + r0 : nullptr;
     p.row_base = r0;
     p.tenant_id = tenant_id;
@@ -452,15 +488,16 @@ int routed_linear_prefill(const bf16_t* X, int64_t M, int d1, int d2, const int3
   return MILORA_OK;
 }
 
-// LoRA shrink of the rows the tile kernel serves (same conditions as prefill_supported).
+// LoRA shrink of the rows the tile kernel serves (same conditions as prefill_supported): t receives
+// kPrefillShrinkParts partial results [part][M][r_max] that routed_linear_prefill adds in part order.
 int launch_shrink_tiles(const bf16_t* X, int64_t M, int d1, const int32_t* row_to_req, const AdapterView& ad, int site,
                         const int32_t* tenant_id, const uint8_t* route, int B, float* t, hipStream_t stream) {
   const int64_t slice = (int64_t)1 << 30;  // rows per launch: the grid index stays well inside 32 bits
   for (int64_t r0 = 0; r0 < M; r0 += slice) {
     const int64_t mc = M - r0 < slice ? M - r0 : slice;
-    hipLaunchKernelGGL(shrink_tiles_kernel, dim3((unsigned)((mc + kShrinkRows - 1) / kShrinkRows)), dim3(256), 0, stream,
-                       X + (size_t)r0 * d1, mc, r0, d1, row_to_req ? row_to_req + r0 : nullptr, ad, site, tenant_id,
-                       route, B, t + (size_t)r0 * ad.r_max);
+    hipLaunchKernelGGL(shrink_tiles_kernel, dim3((unsigned)((mc + kShrinkRows - 1) / kShrinkRows), kShrinkSplit), dim3(256), 0,
+                       stream, X + (size_t)r0 * d1, mc, r0, d1, row_to_req ? row_to_req + r0 : nullptr, ad, site, tenant_id,
+                       route, B, t + (size_t)r0 * ad.r_max, (size_t)M * ad.r_max);
     const int rc = check_launch();
     if (rc) return rc;
   }
