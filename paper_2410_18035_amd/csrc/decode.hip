@@ -56,8 +56,8 @@ constexpr int kLdsBytes = 160 * 1024;       // all of a compute unit's LDS: one 
 template <int MT> struct Cfg;
 template <> struct Cfg<1> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELTA = 8192; };
 template <> struct Cfg<2> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELTA = 8192; };
-template <> struct Cfg<4> { static constexpr int D = 24, NS = 4, CHAIN = 2, DELTA = 8192; };
-template <> struct Cfg<8> { static constexpr int D = 24, NS = 2, CHAIN = 3, DELTA = 2048; };
+template <> struct Cfg<4> { static constexpr int D = 12, NS = 6, CHAIN = 3, DELTA = 8192; };
+template <> struct Cfg<8> { static constexpr int D = 12, NS = 2, CHAIN = 3, DELTA = 2048; };
 
 struct Stage {
   const bf16_t* X;  // input rows: row-major bf16 [M][ldx], or operand blocks (x_packed, see packed_x_offset)
