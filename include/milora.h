@@ -202,6 +202,16 @@ int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
                         size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * milora_packed_workspace_status - the packed-weight kernels (milora_layer_decode and milora_routed_linear
+ * with MILORA_W_PACKED) hand data from one workgroup to another inside a launch and wait for it with bounded
+ * polls; a wait that runs out (it never should) sets a word in the workspace to 1 and the launch finishes with
+ * wrong results instead of hanging.  This call waits for the work queued on `stream`, then copies that word
+ * to *status (host): 0 = every wait ended normally since the workspace was zero-filled.
+ * Errors: EINVAL, EHIP.
+ */
+int milora_packed_workspace_status(const void *workspace, int *status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * milora_layer_decode_profile - measurement aid, not part of the method: runs milora_layer_decode
  * `reps` times on `stream` with a HIP event recorded on that stream after every internal kernel
  * launch, synchronises, and returns the average duration in milliseconds of each launch in

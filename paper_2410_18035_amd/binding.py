@@ -32,7 +32,7 @@ EXPORTS = (
     "milora_route_workspace_bytes", "milora_route",
     "milora_routed_linear_workspace_bytes", "milora_routed_linear_kernel", "milora_routed_linear",
     "milora_layer_decode_workspace_bytes", "milora_layer_decode", "milora_layer_decode_profile",
-    "milora_pack_weight",
+    "milora_pack_weight", "milora_packed_workspace_status",
     "milora_measure_workspace_bytes", "milora_measure_matrix_rate", "milora_measure_read_rate",
 )
 
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.milora_layer_decode_profile.argtypes = L.milora_layer_decode.argtypes + [i32, ctypes.POINTER(ctypes.c_float)]
         L.milora_pack_weight.restype = i32
         L.milora_pack_weight.argtypes = [vp, vp, i32, i32, vp]
+        L.milora_packed_workspace_status.restype = i32
+        L.milora_packed_workspace_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int), vp]
         L.milora_measure_workspace_bytes.restype = sz
         L.milora_measure_workspace_bytes.argtypes = []
         L.milora_measure_matrix_rate.restype = i32
@@ -329,4 +331,13 @@ def milora_measure_read_rate(buf: torch.Tensor, reps: int = 5) -> float:
     rc = lib().milora_measure_read_rate(_dev(buf), nbytes, reps, _dev(ws), ws.numel(), ctypes.byref(out), _stream())
     if rc:
         raise MiloraError(rc, "milora_measure_read_rate")
+    return out.value
+
+
+def milora_packed_workspace_status(workspace: torch.Tensor) -> int:
+    """0 unless a bounded wait inside a packed-weight launch on this workspace ran out (waits for the stream)."""
+    out = ctypes.c_int(-1)
+    rc = lib().milora_packed_workspace_status(_dev(workspace), ctypes.byref(out), _stream())
+    if rc:
+        raise MiloraError(rc, "milora_packed_workspace_status")
     return out.value

@@ -18,6 +18,7 @@ int routed_linear_packed(const bf16_t* X, int M, int d1, int d2, const int32_t* 
 size_t routed_linear_packed_workspace_bytes(int M, int d1, int d2, int r_max);
 int pack_weight(const void* src, void* dst, int d1, int d2, hipStream_t st);
 // prefill.hip
+int decode_workspace_status(const void* workspace, int* status, hipStream_t st);
 bool prefill_supported(int64_t M, int d1, int d2, const void* X, const void* W, const void* Y);
 int launch_shrink_tiles(const bf16_t* X, int64_t M, int d1, const int32_t* row_to_req, const AdapterView& ad, int site,
                         const int32_t* tenant_id, const uint8_t* route, int B, float* t, hipStream_t stream);
@@ -270,6 +271,11 @@ extern "C" int milora_routed_linear(const void* X, int64_t M, int d1, int d2, in
   rc = launch_shrink(X, M, d1, dtype, row_to_req, ad, site, tenant_id, route, B, t, st);
   if (rc) return rc;
   return launch_linear_generic(X, M, d1, d2, dtype, row_to_req, W, bias, ad, site, tenant_id, route, B, t, Y, st);
+}
+
+extern "C" int milora_packed_workspace_status(const void* workspace, int* status, void* stream) {
+  if (!workspace || !status) return MILORA_EINVAL;
+  return decode_workspace_status(workspace, status, (hipStream_t)stream);
 }
 
 extern "C" size_t milora_layer_decode_workspace_bytes(int B, int d, int F, int r_max) {

@@ -1133,6 +1133,15 @@ void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const
 
 size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max) { return carve_decode_ws(nullptr, M, d, F, r_max).bytes; }
 
+// The word the stream kernels set when one of their bounded waits ran out (it lies at the same place in every
+// workspace of the packed paths).  Waits for the stream's work, then copies the word to the host.
+int decode_workspace_status(const void* workspace, int* status, hipStream_t st) {
+  const DecodeWs ws = carve_decode_ws(const_cast<void*>(workspace), 1, 32, 32, 1);
+  MILORA_HIP(hipMemcpyAsync(status, ws.status, sizeof(int), hipMemcpyDeviceToHost, st));
+  MILORA_HIP(hipStreamSynchronize(st));
+  return MILORA_OK;
+}
+
 
 // One decode step of a layer on packed weights: one launch over the stages q,k,v | o | gate,up | down.
 int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer_weights* wts, const AdapterView& ad,

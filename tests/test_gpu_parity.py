@@ -449,6 +449,7 @@ def test_layer_decode_packed_reuses_buffers_across_steps():
                                              flags=oracle.FLAG_RMSNORM if step % 2 == 1 else 0)
         assert_rows_close(qkv, qkv_ref, wl.torch_dtype, f"qkv step {step}")
         assert_rows_close(y, y_ref, wl.torch_dtype, f"y step {step}")
+    assert mb.milora_packed_workspace_status(ws) == 0
 
 
 def test_layer_decode_rowmajor_bf16_matches_too():
@@ -532,6 +533,7 @@ def test_decode_stack_sampled_requests(cfg, sample):
                 worst_free = max(worst_free, float(err))
             xs[s], xr[s] = y, _bf16_bits(y_ref)
         del W, Wp, ad, tab
+    assert mb.milora_packed_workspace_status(ws) == 0  # no hand-over inside the launches timed out
     print(f"{cfg}: worst row error with the same input {worst_same:.2e}, between the free-running chains {worst_free:.2e}")
 
 
