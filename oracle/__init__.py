@@ -174,6 +174,20 @@ def select(logits):
     return route, gap
 
 
+def select_topk(logits, k):
+    """Route bytes and the k-th/(k+1)-th logit gaps for top-k selection (k = 1: site index; k > 1: 0x80 | mask)."""
+    l = np.ascontiguousarray(np.asarray(logits, dtype=np.float64))
+    B = l.shape[0]
+    route = np.empty(B, dtype=np.uint8)
+    gap = np.empty(B, dtype=np.float64)
+    _check(lib().orc_select_topk(_p(l), B, int(k), _p(route), _p(gap)), "select_topk")
+    return route, gap
+
+
+def route_has(route_byte: int, site: int) -> bool:
+    return bool(lib().orc_route_has(ctypes.c_uint8(int(route_byte)), int(site)))
+
+
 @dataclass
 class RouteResult:
     route: np.ndarray  # uint8 [B]
@@ -183,7 +197,7 @@ class RouteResult:
 
 
 def route(H, seq_start, seq_len, tenant_id, Wr, pool_kind=POOL_MEAN, act_kind=ACT_IDENTITY, w_sa=None,
-          act_coef=None) -> RouteResult:
+          act_coef=None, top_k=1) -> RouteResult:
     H = np.ascontiguousarray(H)
     Wr = np.ascontiguousarray(Wr)
     M_tok, d = H.shape
@@ -202,6 +216,8 @@ def route(H, seq_start, seq_len, tenant_id, Wr, pool_kind=POOL_MEAN, act_kind=AC
     rc = lib().orc_route(_p(H), dtype_code(H), ctypes.c_int64(M_tok), d, _p(ss), _p(sl), _p(tid), B, T, _p(Wr),
                          pool_kind, act_kind, _p(w_sa), _p(c), _p(r), _p(logits), _p(gap), _p(h))
     _check(rc, "route")
+    if top_k != 1:
+        r, gap = select_topk(logits, top_k)
     return RouteResult(r, logits, gap, h)
 
 

@@ -218,6 +218,49 @@ void orc_select(const double *logits, int B, uint8_t *route, double *gap) {
   }
 }
 
+/*
+ * A route byte names the sites whose LoRA a request uses: 0..6 = that one site (top-1, the reading the
+ * printed parameter counts fix); 0x80 | mask with bit m of the 7-bit mask set for every chosen site m
+ * (top-k with k > 1: the experiments' text mentions k = 3; the sites' LoRA terms are added without
+ * weights, since the gate of Eq. 3 is never connected to Eq. 1 in the paper); 255 = none.
+ */
+int orc_route_has(uint8_t route, int site) {
+  if (route < ORC_NMOD) return route == site;
+  if (route == 255 || !(route & 0x80)) return 0;
+  return (route >> site) & 1;
+}
+
+/*
+ * Top-k of the softmax for k in 1..6, again taken on the logits: the k largest, an exact tie going to the
+ * lower index.  k = 1 writes the site index like orc_select, k > 1 the mask form.  gap[b] is the distance
+ * between the k-th and the (k+1)-th largest logit (what a rounding error would have to bridge to change the
+ * chosen set).
+ */
+int orc_select_topk(const double *logits, int B, int k, uint8_t *route, double *gap) {
+  if (k < 1 || k >= ORC_NMOD) return ORC_EINVAL;
+  for (int b = 0; b < B; ++b) {
+    const double *l = logits + b * ORC_NMOD;
+    int taken[ORC_NMOD] = {0};
+    int last = -1;
+    for (int q = 0; q < k; ++q) {
+      int best = -1;
+      for (int j = 0; j < ORC_NMOD; ++j)
+        if (!taken[j] && (best < 0 || l[j] > l[best])) best = j;
+      taken[best] = 1;
+      last = best;
+    }
+    double next = -INFINITY;
+    unsigned mask = 0;
+    for (int j = 0; j < ORC_NMOD; ++j) {
+      if (taken[j]) mask |= 1u << j;
+      else if (l[j] > next) next = l[j];
+    }
+    route[b] = k == 1 ? (uint8_t)last : (uint8_t)(0x80u | mask);
+    if (gap) gap[b] = l[last] - next;
+  }
+  return ORC_OK;
+}
+
 /* The whole prompt-aware router of one layer: pool, g, linear, top-1. */
 int orc_route(const void *H, int dtype, int64_t M_tok, int d, const int32_t *seq_start,
               const int32_t *seq_len, const int32_t *tenant_id, int B, int T, const void *Wr,
@@ -264,7 +307,7 @@ int orc_routed_linear(const void *X, int x_dtype, int64_t M, int d1, int d2,
       if (bias) acc += ld(bias, w_dtype, j);
       y[j] = acc;
     }
-    if (route[b] != site) continue;
+    if (!orc_route_has(route[b], site)) continue;
     int t = tenant_id[b];
     if (t < 0 || t >= T) { rc = ORC_ERANGE; continue; }
     int r = rank[t];

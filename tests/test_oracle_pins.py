@@ -192,6 +192,47 @@ def test_sparse_top1_equals_dense_one_hot_mixture():
     assert hits == 5
 
 
+def test_top_k_selection_against_a_stable_sort_and_its_special_cases():
+    rng = np.random.default_rng(12)
+    logits = rng.standard_normal((200, 7))
+    logits[:40] = np.round(logits[:40] * 2) / 2  # many exact ties
+    for k in range(1, 7):
+        route, gap = oracle.select_topk(logits, k)
+        for b in range(200):
+            order = np.argsort(-logits[b], kind="stable")  # ties keep the lower index first
+            chosen = {int(j) for j in order[:k]}
+            got = {m for m in range(7) if oracle.route_has(route[b], m)}
+            assert got == chosen
+            assert gap[b] == logits[b][order[k - 1]] - logits[b][order[k]]
+            assert (route[b] < 7) == (k == 1)
+    r1, g1 = oracle.select_topk(logits, 1)
+    r0, g0 = oracle.select(logits)
+    np.testing.assert_array_equal(r1, r0)
+    np.testing.assert_array_equal(g1, g0)
+    assert not any(oracle.route_has(255, m) for m in range(7))  # "no route" selects nothing
+
+
+def test_set_valued_routes_equal_the_dense_mixture_with_a_multi_hot_gate():
+    """k > 1 (the experiments' text): the chosen sites' LoRA terms are added unweighted."""
+    rng, ad, W, tid, _, d, F = _random_problem(4)
+    logits = rng.standard_normal((5, 7))
+    for k in (2, 3, 6):
+        route, _ = oracle.select_topk(logits, k)
+        gate = np.array([[1.0 if oracle.route_has(route[b], m) else 0.0 for m in range(7)] for b in range(5)])
+        assert (gate.sum(axis=1) == k).all()
+        for site in range(7):
+            d1, _ = oracle.site_dims(site, d, F)
+            X = rng.standard_normal((5, d1))
+            sparse = oracle.routed_linear(X, W[site], ad, site, tid, route)
+            dense = oracle.routed_linear_dense(X, W[site], ad, site, tid, gate)
+            np.testing.assert_allclose(sparse, dense, rtol=0, atol=1e-13 * np.abs(dense).max())
+            # and a request's term at this site is the same as with the single-site route
+            single = oracle.routed_linear(X, W[site], ad, site, tid, np.full(5, site, dtype=np.uint8))
+            base = oracle.routed_linear(X, W[site], ad, site, tid, np.full(5, 255, dtype=np.uint8))
+            for b in range(5):
+                np.testing.assert_array_equal(sparse[b], single[b] if gate[b, site] else base[b])
+
+
 def test_gate_only_at_routed_site_and_own_tenant():
     """Tenant t's B is the constant t+1 and A sums x: the delta reveals which tenant and which rows were used."""
     T, d, F, M = 4, 6, 6, 8
