@@ -44,6 +44,11 @@ extern "C" {
 #define MILORA_MAX_RANK 256       /* largest LoRA rank accepted (the paper sweeps r up to 256, Sec. 4.5) */
 #define MILORA_MAX_DECODE_BATCH 128 /* largest B accepted by milora_layer_decode */
 #define MILORA_ROUTE_NONE 255     /* route value written for a request the router had to skip */
+/* A route byte names the sites whose LoRA term a request uses: 0..6 = that one site (top-1: what the
+ * paper's parameter counts fix, Sec. 4.3); MILORA_ROUTE_SET | mask with bit m of the 7-bit mask set for
+ * every chosen site m (top-k with 1 < k < 7; the chosen sites' terms are added without weights: the
+ * gate of Eq. 3 is not connected to Eq. 1 in the paper); MILORA_ROUTE_NONE = no LoRA term. */
+#define MILORA_ROUTE_SET 0x80
 
 typedef enum {
   MILORA_OK = 0,
@@ -103,8 +108,8 @@ int milora_last_hip_error(void);
  * milora_route - the prompt-aware LoRA router of one layer (Sec. 3.3):
  *   h_b = Pooler(H^l restricted to request b's prompt tokens)        (Eq. 2; last-token / average / max /
  *                                                                     self-attention: softmax_t(H w_sa)^T H, App. C)
- *   route[b] = argmax_j ( g(h_b) W_r^{l, tenant(b)} )_j               (Eq. 3 with top-1)
- * Softmax is increasing, so the top-1 expert is taken on the logits; equal logits resolve to the
+ *   route[b] = the top_k largest of ( g(h_b) W_r^{l, tenant(b)} )_j   (Eq. 3; top_k = 1: argmax)
+ * Softmax is increasing, so the experts are taken on the logits; equal logits resolve to the
  * lowest index.  Pooled state, activation and logits are kept in fp32 whatever `dtype` is.
  * Runs once per layer per prompt; decode never calls it (the decisions are reused, Sec. 3.3).
  *
@@ -118,7 +123,8 @@ int milora_last_hip_error(void);
  *              read for MILORA_POOL_SELFATTN only, NULL otherwise.  d <= 8192 for this pooler.
  *   act_coef   HOST [12] float: a_0..a_6, b_1..b_5 of Ra(x) = (sum_j a_j x^j) / (1 + |sum_i b_i x^i|)
  *              (Sec. 3.4; one set per call, i.e. per layer); read for MILORA_ACT_RATIONAL only, NULL otherwise
- *   route_out  device [B] uint8: selected site per request (row `l` of the caller's route table)
+ *   top_k      1..6: experts per request; 1 writes the site index, more write MILORA_ROUTE_SET | mask
+ *   route_out  device [B] uint8: route byte per request (row `l` of the caller's route table)
  *   logits_out device [B][7] float or NULL: the seven logits
  *   workspace  device, milora_route_workspace_bytes(B, d, M_tok) bytes
  * A request whose span leaves [0, M_tok), whose length is < 1 or whose tenant id is out of range
@@ -130,14 +136,14 @@ size_t milora_route_workspace_bytes(int B, int d, int64_t M_tok);
 int milora_route(const void *H, int64_t M_tok, int d, int dtype, const int32_t *seq_start,
                  const int32_t *seq_len, const int32_t *tenant_id, int B, int n_tenants,
                  const void *Wr, int pool, int act, const void *w_sa, const float *act_coef,
-                 uint8_t *route_out, float *logits_out, void *workspace, size_t workspace_bytes,
-                 void *stream);
+                 int top_k, uint8_t *route_out, float *logits_out, void *workspace,
+                 size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * milora_routed_linear - one LoRA-carrying linear for M rows (Eq. 1 with the layer-level gate of
  * Sec. 3.3: a request's LoRA term is present only at the site its route selected):
  *   b = row_to_req ? row_to_req[m] : m,  t = tenant_id[b]
- *   Y[m] = X[m] W + bias + [route[b] == site] (X[m] W^A_{t,site}) W^B_{t,site}
+ *   Y[m] = X[m] W + bias + [route[b] selects site] (X[m] W^A_{t,site}) W^B_{t,site}
  * Accumulation is fp32; the low-rank intermediate stays fp32 and is added to the fp32 base result
  * before the single rounding to `dtype`.
  *

@@ -24,6 +24,7 @@ ACT = {"identity": 0, "tanh": 1, "relu": 2, "gelu": 3, "rational": 4}
 W_ROWMAJOR, W_PACKED = 0, 1
 LAYER_RMSNORM = 1
 ROUTE_NONE = 255
+ROUTE_SET = 0x80
 MAX_RANK = 256
 MAX_DECODE_BATCH = 128
 
@@ -72,7 +73,7 @@ def lib() -> ctypes.CDLL:
         L.milora_route_workspace_bytes.argtypes = [i32, i32, i64]
         L.milora_route.restype = i32
         L.milora_route.argtypes = [vp, i64, i32, i32, vp, vp, vp, i32, i32, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_float),
-                                   vp, vp, vp, sz, vp]
+                                   i32, vp, vp, vp, sz, vp]
         L.milora_routed_linear_workspace_bytes.restype = sz
         L.milora_routed_linear_workspace_bytes.argtypes = [i64, i32, i32, i32]
         L.milora_routed_linear_kernel.restype = i32
@@ -185,7 +186,7 @@ def milora_route(H: torch.Tensor, seq_start: torch.Tensor, seq_len: torch.Tensor
                  Wr: torch.Tensor, pool: str = "mean", act: str = "identity",
                  route_out: Optional[torch.Tensor] = None, want_logits: bool = True,
                  workspace: Optional[torch.Tensor] = None, w_sa: Optional[torch.Tensor] = None,
-                 act_coef: Optional[Sequence[float]] = None):
+                 act_coef: Optional[Sequence[float]] = None, top_k: int = 1):
     """Prompt-aware router of one layer; returns (route uint8 [B], logits float32 [B,7] or None).
 
     pool "selfattn" needs w_sa [T, d]; act "rational" needs the 12 coefficients a_0..a_6, b_1..b_5."""
@@ -208,7 +209,7 @@ def milora_route(H: torch.Tensor, seq_start: torch.Tensor, seq_len: torch.Tensor
         coef = (ctypes.c_float * 12)(*[float(c) for c in act_coef])
     rc = lib().milora_route(_dev(H), M_tok, d, _dtype_code(H), _dev(seq_start, torch.int32),
                             _dev(seq_len, torch.int32), _dev(tenant_id, torch.int32), B, T, _dev(Wr), POOL[pool],
-                            ACT[act], _dev(w_sa), coef, _dev(route_out, torch.uint8), _dev(logits), _dev(workspace),
+                            ACT[act], _dev(w_sa), coef, top_k, _dev(route_out, torch.uint8), _dev(logits), _dev(workspace),
                             workspace.numel(), _stream())
     if rc != 0:
         raise MiloraError(rc, "milora_route")

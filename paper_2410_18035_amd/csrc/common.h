@@ -80,11 +80,18 @@ inline AdapterView view_of(const milora_adapters* a) {
   return AdapterView{a->rank, a->A, a->B, a->n_tenants, a->r_max};
 }
 
+// Does a route byte select `site`?  0..6 name one site, 0x80 | mask a set of sites (bit m = site m), 255 none.
+__host__ __device__ __forceinline__ bool route_has(uint8_t route, int site) {
+  if (route < MILORA_NUM_SITES) return route == site;
+  if (route == MILORA_ROUTE_NONE || !(route & 0x80)) return false;
+  return ((route >> site) & 1) != 0;
+}
+
 // Rank of the LoRA term of request `b` at `site`, or 0 when the request carries none there
 // (not routed to the site, or an id out of range).
 __device__ __forceinline__ int routed_rank(const AdapterView& ad, const int32_t* tenant_id, const uint8_t* route,
                                            int b, int B, int site, int* tenant) {
-  if (b < 0 || b >= B || route[b] != site) return 0;
+  if (b < 0 || b >= B || !route_has(route[b], site)) return 0;
   int t = tenant_id[b];
   if (t < 0 || t >= ad.n_tenants) return 0;
   int r = ad.rank[t];

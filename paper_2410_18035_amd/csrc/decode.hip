@@ -87,10 +87,11 @@ struct Params {
   const uint8_t* route;
   const int32_t* row_to_req;
   int lora;
-  float* tpart;   // [M][nc_max][r_max] shrink partials t = x[chunk] . A[chunk]
-  float* tfin;    // [M][r_max] t = x . A: the partials summed in chunk order by the wave that wrote the last one
-  int* tcount;    // [M] partials of the row written so far in this launch; zero between launches
-  int* tready;    // [M] epoch of the launch whose t is in tfin
+  // LoRA shrinks, one slot per (row, site position inside its level): slot = row * 3 + position
+  float* tpart;   // [slots][nc_max][r_max] shrink partials t = x[chunk] . A[chunk]
+  float* tfin;    // [slots][r_max] t = x . A: the partials summed in chunk order by the wave that wrote the last one
+  int* tcount;    // [slots] partials written so far in this launch; zero between launches
+  int* tready;    // [slots] launch epoch * 16 + (stage that ran the shrink) + 1 of the t in tfin
   int nc_max;
   int* flags;     // [kMaxGrid] grid barrier flags, monotone
   int* status;    // set to 1 when a bounded wait ran out
@@ -115,10 +116,11 @@ struct Ctrl {
   int s_flag;
   float ss_part[kSW][kMaxRows];
   float inv_rows[kMaxRows];
-  int l_m[kMaxRows], l_r[kMaxRows], l_t[kMaxRows], l_s[kMaxRows];
-  // what the route table says about each row, looked up once per launch: site (-1: no LoRA term), tenant, rank
-  int r_site[kMaxRows], r_ten[kMaxRows], r_rank[kMaxRows];
-  int s_rows[kMaxRows];  // rows with a shrink in the current level
+  int l_ms[3 * kMaxRows];  // LoRA terms that land in this workgroup's tiles: row | site position << 8
+  // what the route table says about each row, looked up once per launch: the sites with a LoRA term (bit m =
+  // site m, 0: none), tenant, rank
+  int r_mask[kMaxRows], r_ten[kMaxRows], r_rank[kMaxRows];
+  int s_rows[3 * kMaxRows];  // shrinks of the current level: row | site position << 8
   int s_cnt;
 };
 static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
@@ -215,8 +217,9 @@ __device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, i
 
 // ---- one LoRA shrink item by one wave: partial t of row m over one k chunk ---------------------------
 template <int MT>
-__device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& sg, int m, int site, int tenant, int r,
-                                                 int kc, int NC, int epoch, int lane) {
+__device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& sg, int m, int pos, int tenant, int r,
+                                                 int kc, int NC, int tag, int lane) {
+  const int site = sg.site[pos], slot = m * 3 + pos;
   const gbf16* A = (const gbf16*)p.ad.A[tenant * MILORA_NUM_SITES + site];
   const int K = sg.K, rmax = p.ad.r_max;
   const int k_lo = kc * kShrinkChunk;
@@ -227,7 +230,7 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
   auto xval = [&](int k) __attribute__((always_inline)) -> float {
     return bf16_to_f32(Xp[xpk ? packed_x_offset(m, k, MT) : (size_t)m * xld + k]);
   };
-  float* row_part = p.tpart + ((size_t)m * p.nc_max) * rmax;
+  float* row_part = p.tpart + ((size_t)slot * p.nc_max) * rmax;
   float* out = row_part + (size_t)kc * rmax;
   const int lpr = r >> 3;  // lanes per row of A when r is a multiple of 8
   if ((r & 7) == 0 && (lpr & (lpr - 1)) == 0 && lpr <= 32 && ((uintptr_t)A & 15) == 0) {
@@ -281,7 +284,7 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
   // of the sum is fixed) and publishes t; every workgroup with a tile of the site reads it from there.
   wait_all_mem();
   int done = 0;
-  if (lane == 0) done = __hip_atomic_fetch_add(&p.tcount[m], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+  if (lane == 0) done = __hip_atomic_fetch_add(&p.tcount[slot], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
   done = __builtin_amdgcn_readfirstlane(done);
   if (done == NC) {
     for (int c = lane; c < r; c += 64) {
@@ -294,12 +297,12 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
 #pragma unroll
         for (int u = 0; u < 8; ++u) t += k0 + u < NC ? v[u] : 0.f;
       }
-      st_agent(p.tfin + (size_t)m * rmax + c, t);
+      st_agent(p.tfin + (size_t)slot * rmax + c, t);
     }
     wait_all_mem();
     if (lane == 0) {
-      st_agent(&p.tcount[m], 0);
-      st_agent(&p.tready[m], epoch);
+      st_agent(&p.tcount[slot], 0);
+      st_agent(&p.tready[slot], tag);
     }
   }
 }
@@ -380,18 +383,19 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   }
   if (tid >= 64 && tid < 64 + kMaxRows) {
     const int m = tid - 64;
-    int site = -1, tenant = 0, r = 0;
+    int mask = 0, tenant = 0, r = 0;
     if (m < p.M && p.lora) {
       const int req = p.row_to_req ? p.row_to_req[m] : m;
       if (req >= 0 && req < p.Breq) {
-        const int st = p.route[req];
-        if (st < MILORA_NUM_SITES) {
-          r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, st, &tenant);
-          if (r > 0) site = st;
-        }
+        const uint8_t rb = p.route[req];
+        for (int st = 0; st < MILORA_NUM_SITES; ++st)
+          if (route_has(rb, st)) {
+            r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, st, &tenant);  // the same for every chosen site
+            if (r > 0) mask |= 1 << st;
+          }
       }
     }
-    c.r_site[m] = site;
+    c.r_mask[m] = mask;
     c.r_ten[m] = tenant;
     c.r_rank[m] = r;
   }
@@ -647,23 +651,22 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   };
   // LoRA expand of list entries [l0, l1): lane = (entry, tile, column quad); added to `red` or stored in `delta`
   // shrink t[c] of row m, as published by the wave that summed the row's partials
-  auto t_sum = [&](int m, int c, int NC) __attribute__((always_inline)) -> float {
-    (void)NC;
-    return ld_agent(p.tfin + (size_t)m * p.ad.r_max + c);
+  auto t_sum = [&](int m, int s, int c) __attribute__((always_inline)) -> float {
+    return ld_agent(p.tfin + (size_t)(m * 3 + s) * p.ad.r_max + c);
   };
   auto expand = [&](const int L, const Stage& sg, const int NS, const int NC, int l0, int l1, bool to_red) __attribute__((always_inline)) {
     const int work = (l1 - l0) * NS * 4;
     for (int e = lane; e < work; e += 64) {
       const int q = e & 3, a = (e >> 2) % NS, li = l0 + (e >> 2) / NS;
-      const int s = c.l_s[li];
+      const int s = c.l_ms[li] >> 8;
       float d[4] = {0.f, 0.f, 0.f, 0.f};
       const bool mine = c.tb_seg[L][a] == s;
-      const int m = c.l_m[li];
+      const int m = c.l_ms[li] & 0xff;
       if (mine) {
-        const int r = c.l_r[li];
+        const int r = c.r_rank[m];
         const int n = c.tb_tile[L][a] * 16 + q * 4;
         const size_t ldb = (size_t)sg.N[s];
-        const gbf16* Bm = (const gbf16*)p.ad.B[c.l_t[li] * MILORA_NUM_SITES + sg.site[s]] + n;
+        const gbf16* Bm = (const gbf16*)p.ad.B[c.r_ten[m] * MILORA_NUM_SITES + sg.site[s]] + n;
         const float* tv = t_lds + (size_t)li * p.ad.r_max;  // entries formed ahead of the stage end have t in LDS
         if (((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0) {
           int cc = 0;
@@ -673,7 +676,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
               bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(cc + u) * ldb);
-              t[u] = to_red ? t_sum(m, cc + u, NC) : tv[cc + u];
+              t[u] = to_red ? t_sum(m, s, cc + u) : tv[cc + u];
             }
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
@@ -685,7 +688,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
           }
           for (; cc < r; ++cc) {
             const u32x2 bb = *reinterpret_cast<const gu32x2*>(Bm + (size_t)cc * ldb);
-            const float t = to_red ? t_sum(m, cc, NC) : tv[cc];
+            const float t = to_red ? t_sum(m, s, cc) : tv[cc];
             d[0] += t * __uint_as_float(bb[0] << 16);
             d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
             d[2] += t * __uint_as_float(bb[1] << 16);
@@ -693,7 +696,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
           }
         } else {
           for (int cc = 0; cc < r; ++cc) {
-            const float t = to_red ? t_sum(m, cc, NC) : tv[cc];
+            const float t = to_red ? t_sum(m, s, cc) : tv[cc];
 #pragma unroll
             for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)cc * ldb + z]);
           }
@@ -862,11 +865,13 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     }
   } else {
     // ===================================== LoRA wave =====================================
+    int lvl_tag = 0;
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
       const int K = sg.K;
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
       const int NC = shrink_chunks(K);
+      if (sg.lora_shrink) lvl_tag = epoch * 16 + L + 1;  // a slot can serve several levels of one launch
       if (p.lora && sg.lora_shrink) {
         if (sg.sync_before && L > 0) {
           if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
@@ -874,25 +879,22 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         // the rows with a LoRA term at one of this level's sites, in row order (the same list in every workgroup)
         if (lane == 0) c.s_cnt = 0;
         wave_sync();
-        for (int m0 = 0; m0 < p.M; m0 += 64) {
-          const int m = m0 + lane;
-          bool has = false;
-          if (m < p.M) {
-            const int st = c.r_site[m];
-            for (int s = 0; s < sg.n_seg; ++s) has = has || (st >= 0 && sg.site[s] == st);
+        for (int s = 0; s < sg.n_seg; ++s)
+          for (int m0 = 0; m0 < p.M; m0 += 64) {
+            const int m = m0 + lane;
+            const bool has = m < p.M && ((c.r_mask[m] >> sg.site[s]) & 1);
+            const unsigned long long mask = __ballot(has);
+            const int base = c.s_cnt;
+            if (has) c.s_rows[base + __popcll(mask & ((1ull << lane) - 1ull))] = m | (s << 8);
+            wave_sync();
+            if (lane == 0) c.s_cnt = base + __popcll(mask);
+            wave_sync();
           }
-          const unsigned long long mask = __ballot(has);
-          const int base = c.s_cnt;
-          if (has) c.s_rows[base + __popcll(mask & ((1ull << lane) - 1ull))] = m;
-          wave_sync();
-          if (lane == 0) c.s_cnt = base + __popcll(mask);
-          wave_sync();
-        }
         const int items = c.s_cnt * NC;
         // spread the items of consecutive rows over the grid, and of consecutive stages over different workgroups
         for (int it = (wg + 97 * L) % G; it < items; it += G) {
-          const int m = c.s_rows[it / NC];
-          lora_shrink_item<MT>(p, sg, m, c.r_site[m], c.r_ten[m], c.r_rank[m], it % NC, NC, epoch, lane);
+          const int ms = c.s_rows[it / NC], m = ms & 0xff;
+          lora_shrink_item<MT>(p, sg, m, ms >> 8, c.r_ten[m], c.r_rank[m], it % NC, NC, lvl_tag, lane);
         }
       }
       if (kLoaders > 1) {
@@ -909,15 +911,14 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         if (lane == 0) c.l_cnt = 0;
         wave_sync();
         for (int m = lane; m < p.M; m += 64) {
-          const int site = c.r_site[m];
-          if (site >= 0) {
+          const int sites = c.r_mask[m];
+          if (sites) {
             for (int s = 0; s < sg.n_seg; ++s) {
-              if (sg.site[s] != site) continue;
+              if (!((sites >> sg.site[s]) & 1)) continue;
               bool mine = false;  // does the workgroup hold a tile of this site?
               for (int a = 0; a < NS; ++a) mine = mine || c.tb_seg[L][a] == s;
               if (!mine) continue;
-              const int idx = atomicAdd(&c.l_cnt, 1);
-              c.l_m[idx] = m; c.l_r[idx] = c.r_rank[m]; c.l_t[idx] = c.r_ten[m]; c.l_s[idx] = s;
+              c.l_ms[atomicAdd(&c.l_cnt, 1)] = m | (s << 8);
             }
           }
         }
@@ -927,8 +928,9 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         {
           int spins = 0;
           for (int e = lane; e < ((cnt + 63) & ~63); e += 64) {
-            const int* f = p.tready + c.l_m[e < cnt ? e : 0];
-            while (!__all(e >= cnt || ld_agent(f) == epoch)) {
+            const int ms = c.l_ms[e < cnt ? e : 0];
+            const int* f = p.tready + (ms & 0xff) * 3 + (ms >> 8);
+            while (!__all(e >= cnt || ld_agent(f) == lvl_tag)) {
               if (++spins >= kSpinLimit) { *p.status = 1; break; }
               __builtin_amdgcn_s_sleep(2);
             }
@@ -939,7 +941,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         npre = npre < cap_t ? npre : cap_t;
         for (int e = lane; e < npre * p.ad.r_max; e += 64) {
           const int li = e / p.ad.r_max, cc = e - li * p.ad.r_max;
-          t_lds[e] = cc < c.l_r[li] ? t_sum(c.l_m[li], cc, NC) : 0.f;
+          const int ms = c.l_ms[li];
+          t_lds[e] = cc < c.r_rank[ms & 0xff] ? t_sum(ms & 0xff, ms >> 8, cc) : 0.f;
         }
         wave_sync();
         expand(L, sg, NS, NC, 0, npre, false);
@@ -957,8 +960,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         const int work = npre * NS * 4;
         for (int e = lane; e < work; e += 64) {
           const int q = e & 3, a = (e >> 2) % NS, li = (e >> 2) / NS;
-          if (c.tb_seg[L][a] != c.l_s[li]) continue;
-          const int m = c.l_m[li];
+          if (c.tb_seg[L][a] != (c.l_ms[li] >> 8)) continue;
+          const int m = c.l_ms[li] & 0xff;
 #pragma unroll
           for (int z = 0; z < 4; ++z) red[red_idx(a, m, q * 4 + z)] += delta[((li * NS + a) * 4 + q) * 4 + z];
         }
@@ -1091,10 +1094,10 @@ bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_ma
 struct DecodeWs {
   int* flags;      // [kMaxGrid] barrier flags; zero before the first launch, then owned by the kernels
   int* status;
-  int* tready;     // [M] epoch of the launch that published the row's shrink
-  int* tcount;     // [M] partials written so far (zero between launches)
-  float* tfin;     // [M][r_max] published shrinks
-  float* tpart;    // [M][NCmax][r_max] shrink partials
+  int* tready;     // [3 kMaxRows] per shrink slot: epoch of the launch that published it
+  int* tcount;     // [3 kMaxRows] partials written so far (zero between launches)
+  float* tfin;     // [3 M][r_max] published shrinks
+  float* tpart;    // [3 M][NCmax][r_max] shrink partials
   float* h_f32;    // [M][d]
   bf16_t* v_pk;    // a = v as operand blocks   (K = d)
   bf16_t* h_pk;    // h as operand blocks       (K = d)
@@ -1107,9 +1110,9 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
   size_t off = 0;
   auto take = [&](size_t n) { size_t o = off; off += align_up(n, 256); return o; };
   const size_t o_fl = take((size_t)(kMaxGrid + 64) * sizeof(int));
-  const size_t o_p = take((size_t)kMaxRows * 2 * sizeof(int));  // at a fixed place whatever M is: the counters must read zero
-  const size_t o_tf = take((size_t)M * r_max * sizeof(float));
-  const size_t o_t = take((size_t)M * shrink_chunks(big) * r_max * sizeof(float));
+  const size_t o_p = take((size_t)kMaxRows * 6 * sizeof(int));  // at a fixed place whatever M is: the counters must read zero
+  const size_t o_tf = take((size_t)3 * M * r_max * sizeof(float));
+  const size_t o_t = take((size_t)3 * M * shrink_chunks(big) * r_max * sizeof(float));
   const size_t o_h = take((size_t)M * d * sizeof(float));
   const int rows = mt_for(M) * 16;
   const size_t o_v = take((size_t)rows * d * sizeof(bf16_t));
@@ -1117,7 +1120,7 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
   const size_t o_m = take((size_t)rows * F * sizeof(bf16_t));
   char* b = (char*)base;
   int* fl = (int*)(b + o_fl);
-  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (int*)(b + o_p) + kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
+  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (int*)(b + o_p) + 3 * kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
                   (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb), (bf16_t*)(b + o_m), off};
 }
 

@@ -263,7 +263,7 @@ __global__ void __launch_bounds__(kFinishThreads) route_finish_kernel(const T* _
                                                                       const int32_t* __restrict__ seq_len,
                                                                       const int32_t* __restrict__ tenant_id,
                                                                       int T_tenants, const T* __restrict__ Wr, int pool,
-                                                                      int act, RationalCoef coef, int S,
+                                                                      int act, RationalCoef coef, int top_k, int S,
                                                                       const float* __restrict__ partial,
                                                                       const float* __restrict__ ml,
                                                                       uint8_t* __restrict__ route_out,
@@ -354,15 +354,23 @@ __global__ void __launch_bounds__(kFinishThreads) route_finish_kernel(const T* _
   __syncthreads();
   if (threadIdx.x == 0) {
     float logit[MILORA_NUM_SITES];
-    int best = 0;
     for (int j = 0; j < MILORA_NUM_SITES; ++j) {
       float v = 0.f;
       for (int wv = 0; wv < kFinishThreads / 64; ++wv) v += wsum[wv][j];
       logit[j] = v;
-      if (v > logit[best]) best = j;
       if (logits_out) logits_out[b * MILORA_NUM_SITES + j] = v;
     }
-    route_out[b] = (uint8_t)best;
+    // the top_k largest logits, an exact tie going to the lower index
+    unsigned mask = 0;
+    int last = 0;
+    for (int q = 0; q < top_k; ++q) {
+      int best = -1;
+      for (int j = 0; j < MILORA_NUM_SITES; ++j)
+        if (!((mask >> j) & 1) && (best < 0 || logit[j] > logit[best])) best = j;
+      mask |= 1u << best;
+      last = best;
+    }
+    route_out[b] = top_k == 1 ? (uint8_t)last : (uint8_t)(0x80u | mask);
   }
 }
 
@@ -413,8 +421,9 @@ extern "C" size_t milora_route_workspace_bytes(int B, int d, int64_t M_tok) {
 
 extern "C" int milora_route(const void* H, int64_t M_tok, int d, int dtype, const int32_t* seq_start,
                             const int32_t* seq_len, const int32_t* tenant_id, int B, int n_tenants, const void* Wr,
-                            int pool, int act, const void* w_sa, const float* act_coef, uint8_t* route_out,
-                            float* logits_out, void* workspace, size_t workspace_bytes, void* stream) {
+                            int pool, int act, const void* w_sa, const float* act_coef, int top_k,
+                            uint8_t* route_out, float* logits_out, void* workspace, size_t workspace_bytes,
+                            void* stream) {
   if (!H || !seq_start || !seq_len || !tenant_id || !Wr || !route_out) return MILORA_EINVAL;
   if (M_tok < 1 || d < 1 || B < 1 || n_tenants < 1) return MILORA_EINVAL;
   if (dtype != MILORA_BF16 && dtype != MILORA_F32) return MILORA_EINVAL;
@@ -422,6 +431,7 @@ extern "C" int milora_route(const void* H, int64_t M_tok, int d, int dtype, cons
   if (act < MILORA_ACT_IDENTITY || act > MILORA_ACT_RATIONAL) return MILORA_EINVAL;
   if (pool == MILORA_POOL_SELFATTN && !w_sa) return MILORA_EINVAL;
   if (act == MILORA_ACT_RATIONAL && !act_coef) return MILORA_EINVAL;
+  if (top_k < 1 || top_k >= MILORA_NUM_SITES) return MILORA_EINVAL;
   if (B > 65535) return MILORA_ERANGE;
   if (pool == MILORA_POOL_SELFATTN && d > kSelfAttnMaxD) return MILORA_ERANGE;
   hipStream_t st = (hipStream_t)stream;
@@ -461,11 +471,11 @@ extern "C" int milora_route(const void* H, int64_t M_tok, int d, int dtype, cons
   }
   if (dtype == MILORA_BF16)
     hipLaunchKernelGGL((route_finish_kernel<bf16_t>), dim3(B), dim3(kFinishThreads), 0, st, (const bf16_t*)H, M_tok, d,
-                       seq_start, seq_len, tenant_id, n_tenants, (const bf16_t*)Wr, pool, act, coef, S, partial, ml,
+                       seq_start, seq_len, tenant_id, n_tenants, (const bf16_t*)Wr, pool, act, coef, top_k, S, partial, ml,
                        route_out, logits_out);
   else
     hipLaunchKernelGGL((route_finish_kernel<float>), dim3(B), dim3(kFinishThreads), 0, st, (const float*)H, M_tok, d,
-                       seq_start, seq_len, tenant_id, n_tenants, (const float*)Wr, pool, act, coef, S, partial, ml,
+                       seq_start, seq_len, tenant_id, n_tenants, (const float*)Wr, pool, act, coef, top_k, S, partial, ml,
                        route_out, logits_out);
   return check_launch();
 }

@@ -67,7 +67,7 @@ def test_argument_validation_happens_before_any_device_work():
     L = mb.lib()
     null = ctypes.c_void_p(None)
     # null tensors
-    assert L.milora_route(null, 10, 8, 0, null, null, null, 1, 1, null, 0, 0, null, None, null, null, null, 0, null) == -1
+    assert L.milora_route(null, 10, 8, 0, null, null, null, 1, 1, null, 0, 0, null, None, 1, null, null, null, 0, null) == -1
     ad = mb._Adapters(1, 8, 0, 0, 0)
     assert L.milora_routed_linear(null, 1, 8, 8, 0, null, null, 0, null, ctypes.byref(ad), 0, null, null, 1, null,
                                   null, 0, null) == -1
@@ -77,12 +77,13 @@ def test_argument_validation_happens_before_any_device_work():
     assert L.milora_pack_weight(null, null, 32, 16, null) == -1
     # fake non-null pointers never get dereferenced on these paths: bad enum, bad site, missing workspace
     p = ctypes.c_void_p(0x1000)
-    assert L.milora_route(p, 10, 8, 7, p, p, p, 1, 1, p, 0, 0, null, None, p, null, p, 1 << 20, null) == -1  # dtype 7
-    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 4, 0, null, None, p, null, p, 1 << 20, null) == -1  # pool 4
-    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 3, 0, null, None, p, null, p, 1 << 20, null) == -1  # no w_sa
-    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 4, null, None, p, null, p, 1 << 20, null) == -1  # no coefficients
-    assert L.milora_route(p, 10, 9000, 0, p, p, p, 1, 1, p, 3, 0, p, None, p, null, p, 1 << 30, null) == -2  # d too large
-    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 0, null, None, p, null, null, 0, null) == -5  # no workspace
+    assert L.milora_route(p, 10, 8, 7, p, p, p, 1, 1, p, 0, 0, null, None, 1, p, null, p, 1 << 20, null) == -1  # dtype 7
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 4, 0, null, None, 1, p, null, p, 1 << 20, null) == -1  # pool 4
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 3, 0, null, None, 1, p, null, p, 1 << 20, null) == -1  # no w_sa
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 4, null, None, 1, p, null, p, 1 << 20, null) == -1  # no coefficients
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 0, null, None, 7, p, null, p, 1 << 20, null) == -1  # top_k 7
+    assert L.milora_route(p, 10, 9000, 0, p, p, p, 1, 1, p, 3, 0, p, None, 1, p, null, p, 1 << 30, null) == -2  # d too large
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 0, null, None, 1, p, null, null, 0, null) == -5  # no workspace
     ad = mb._Adapters(1, 8, 0x1000, 0x1000, 0x1000)
     assert L.milora_routed_linear(p, 1, 8, 8, 0, null, p, 0, null, ctypes.byref(ad), 9, p, p, 1, p, p, 1 << 20,
                                   null) == -1  # site 9

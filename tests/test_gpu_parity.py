@@ -479,6 +479,62 @@ def test_headline_shape_one_step_full_parity():
     print(f"7B layer: excluded routes {excluded:.3f}, worst row rel err {worst:.3e}")
 
 
+# ------------------------------------------------------------------------------------------- several experts per request
+def _route_sets(B, k, seed):
+    """Route bytes MILORA_ROUTE_SET | mask with k sites each, drawn per request (the table is an input of decode)."""
+    g = torch.Generator().manual_seed(seed)
+    out = torch.empty(B, dtype=torch.uint8)
+    for b in range(B):
+        sites = torch.randperm(7, generator=g)[:k].tolist()
+        out[b] = mb.ROUTE_SET | sum(1 << m for m in sites)
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("k", [2, 3, 6])
+def test_route_top_k(dtype, k):
+    wl = small(dtype=dtype, d=520, T=5, B=23, prompt_len=(1, 200), tenants="uniform", seed=100 + k)
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl).to(DEV)
+    route, logits = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, "mean", "tanh", top_k=k)
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), oracle.POOL_MEAN, oracle.ACT_TANH,
+                       top_k=k)
+    excluded = assert_routes_match(route, ref, wl.torch_dtype)  # gap = k-th minus (k+1)-th logit
+    assert excluded <= 0.15
+    got = route.cpu().numpy()
+    assert ((got & mb.ROUTE_SET) != 0).all() and all(bin(int(v) & 0x7f).count("1") == k for v in got)
+
+
+@pytest.mark.parametrize("layout,M", [(mb.W_ROWMAJOR, 9), (mb.W_PACKED, 9), (mb.W_ROWMAJOR, 300), (mb.W_PACKED, 140)])
+def test_routed_linear_with_route_sets(layout, M):
+    """Requests that use the LoRA of several sites: every kernel of the routed linear (any-shape, weight-streaming,
+    matrix-core tiles) adds the term wherever the request's set holds the site."""
+    wl = small(dtype="bf16", d=256, F=352, T=4, B=9, ranks=(8, 16), tenants="uniform", seed=61)
+    route = _route_sets(wl.B, 3, 7)
+    route[0] = mb.ROUTE_NONE
+    route[1] = 5  # single-site bytes keep working beside sets
+    g = torch.Generator().manual_seed(8)
+    r2r = None if M == wl.B else torch.randint(0, wl.B, (M,), generator=g)
+    for site in (0, 5, 6):
+        Y, ref = _linear_case(wl, site, M=M, row_to_req=r2r, w_layout=layout, route=route, seed=site)
+        assert_rows_close(Y, ref, torch.bfloat16, f"site {site}")
+    hit = [oracle.route_has(int(route[b]), 5) for b in range(wl.B)]
+    assert any(hit) and not all(hit)
+
+
+@pytest.mark.parametrize("B,k", [(7, 2), (32, 3), (64, 3), (100, 6)])
+def test_layer_decode_with_route_sets(B, k):
+    """Decode with k experts per request: several LoRA terms of one request inside one level (q, k and v; gate and
+    up) and across levels."""
+    wl = small(dtype="bf16", d=512, F=1056, T=6, B=B, ranks=(8, 32, 64), tenants="uniform", seed=200 + B)
+    route = _route_sets(B, k, B)
+    route[0] = 3
+    route[B - 1] = mb.ROUTE_NONE
+    assert _layer_case(wl, True, mb.W_PACKED, route=route) <= TOL[torch.bfloat16]
+    assert _layer_case(wl, False, mb.W_ROWMAJOR, route=route) <= TOL[torch.bfloat16]
+
+
 # ------------------------------------------------------------------------------------------- layer stacks
 def _bf16_bits(y64):
     """fp64 -> the bf16 the method would store between layers, as the oracle's input bit pattern."""
