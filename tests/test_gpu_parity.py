@@ -452,6 +452,46 @@ def test_layer_decode_packed_reuses_buffers_across_steps():
     assert mb.milora_packed_workspace_status(ws) == 0
 
 
+def test_layer_decode_in_a_hip_graph_replays_like_eager():
+    """The serving loop captures the decode step once and replays it: every replay, with eager work and
+    synchronisations in between, must give bit for bit what the eager call gives on the same input."""
+    wl = small(dtype="bf16", d=1024, F=2752, T=8, B=32, ranks=(16, 32), tenants="uniform", seed=72)
+    W, ad, tab = device_layer(wl)
+    Wd = [mb.milora_pack_weight(w) for w in W]
+    tid = synth.tenant_ids(wl).to(DEV)
+    g = torch.Generator().manual_seed(6)
+    route = torch.randint(0, 7, (wl.B,), generator=g).to(torch.uint8).to(DEV)
+    ws = torch.zeros(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, tab.r_max), dtype=torch.uint8, device=DEV)
+    x = synth.decode_input(wl, 0, DEV).clone()
+    y = torch.empty_like(x)
+    qkv = torch.empty(wl.B, 3 * wl.d, dtype=x.dtype, device=DEV)
+
+    def step():
+        mb.milora_layer_decode(x, Wd, tab, tid, route, wl.F, w_layout=mb.W_PACKED, rmsnorm=True, y=y, qkv_out=qkv,
+                               workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        x.copy_(synth.decode_input(wl, 10 + rep, DEV))
+        step()
+        torch.cuda.synchronize()
+        y_eager, qkv_eager = y.clone(), qkv.clone()
+        y.zero_()
+        qkv.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager) and torch.equal(qkv, qkv_eager), f"replay {rep}"
+    assert mb.milora_packed_workspace_status(ws) == 0
+
+
 def test_layer_decode_rowmajor_bf16_matches_too():
     wl = small(dtype="bf16", d=256, F=352, T=4, B=9, ranks=(8,), tenants="uniform", seed=51)
     _layer_case(wl, True, mb.W_ROWMAJOR)
