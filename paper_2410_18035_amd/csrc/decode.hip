@@ -211,7 +211,11 @@ __device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, i
     if (++spins >= kSpinLimit) return false;
     __builtin_amdgcn_s_sleep(2);
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  // No cache invalidation here: what later stages read (the packed activations, the fp32 residual) is written
+  // once per launch, with write-through stores, before anybody reads it in that launch, and a launch starts
+  // with clean caches - so neither L2 nor L1 can hold an older copy.  (An acquire fence at this point throws away
+  // the XCD's L2 lines of the stage input that the workgroups ahead of this one have just fetched.)
+  compiler_fence();
   return true;
 }
 
