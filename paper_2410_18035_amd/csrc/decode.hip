@@ -716,11 +716,51 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       }
     }
   };
+  // bias + residual of a lane's first output item, fetched while the stage still runs (the stages that have them,
+  // o and down, give a lane at most one item per tile and row tile: the loads are off the stage end's path)
+  auto glue_prefetch = [&](const int L, const Stage& sg, const int NS, const int half, float (&pre)[8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int z = 0; z < 8; ++z) pre[z] = 0.f;
+    const int nout = sg.pair ? NS >> 1 : NS;
+    const int e = half * 64 + lane;
+    if (e >= nout * p.M * 2) return;
+    const int hf = e & 1, m = (e >> 1) % p.M, ao = (e >> 1) / p.M;
+    const int a = sg.pair ? 2 * ao : ao;
+    if (c.tb_seg[L][a] < 0) return;
+    const int s = sg.pair ? 0 : c.tb_seg[L][a];
+    const int n = c.tb_tile[L][a] * 16 + hf * 8;
+    if (sg.bias[s]) {
+      const u32x4 bb = *reinterpret_cast<const u32x4*>(sg.bias[s] + n);
+#pragma unroll
+      for (int z = 0; z < 4; ++z) {
+        pre[2 * z] += __uint_as_float(bb[z] << 16);
+        pre[2 * z + 1] += __uint_as_float(bb[z] & 0xffff0000u);
+      }
+    }
+    if (sg.resid_bf16) {
+      const u32x4 rr = *reinterpret_cast<const u32x4*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + n);
+#pragma unroll
+      for (int z = 0; z < 4; ++z) {
+        pre[2 * z] += __uint_as_float(rr[z] << 16);
+        pre[2 * z + 1] += __uint_as_float(rr[z] & 0xffff0000u);
+      }
+    }
+    if (sg.resid_f32) {
+      const f32x4* rr = reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + n);
+      const f32x4 r0 = rr[0], r1 = rr[1];
+#pragma unroll
+      for (int z = 0; z < 4; ++z) {
+        pre[z] += r0[z];
+        pre[4 + z] += r1[z];
+      }
+    }
+  };
   // glue and stores of half of the outputs: lane = (output tile, row, half of the tile's 16 columns)
-  auto glue = [&](const int L, const Stage& sg, const int NS, const int half) __attribute__((always_inline)) {
+  auto glue = [&](const int L, const Stage& sg, const int NS, const int half, const float (&pre)[8]) __attribute__((always_inline)) {
     const int nout = sg.pair ? NS >> 1 : NS;
     const int work = nout * p.M * 2;
     for (int e = half * 64 + lane; e < work; e += 128) {
+      const bool first = e < 128;
       const int hf = e & 1, m = (e >> 1) % p.M, ao = (e >> 1) / p.M;
       const int a = sg.pair ? 2 * ao : ao;
       if (c.tb_seg[L][a] < 0) continue;  // filler tile: streamed to keep the ring rounds whole, result dropped
@@ -734,29 +774,34 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         if (sg.pair) val[z] = silu(v0) * (red[red_idx(a + 1, m, hf * 8 + z)] * inv);
         else val[z] = v0;
       }
-      if (sg.bias[s]) {
-        const u32x4 bb = *reinterpret_cast<const u32x4*>(sg.bias[s] + n);
+      if (first) {
 #pragma unroll
-        for (int z = 0; z < 4; ++z) {
-          val[2 * z] += __uint_as_float(bb[z] << 16);
-          val[2 * z + 1] += __uint_as_float(bb[z] & 0xffff0000u);
+        for (int z = 0; z < 8; ++z) val[z] += pre[z];
+      } else {
+        if (sg.bias[s]) {
+          const u32x4 bb = *reinterpret_cast<const u32x4*>(sg.bias[s] + n);
+#pragma unroll
+          for (int z = 0; z < 4; ++z) {
+            val[2 * z] += __uint_as_float(bb[z] << 16);
+            val[2 * z + 1] += __uint_as_float(bb[z] & 0xffff0000u);
+          }
         }
-      }
-      if (sg.resid_bf16) {
-        const u32x4 rr = *reinterpret_cast<const u32x4*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + n);
+        if (sg.resid_bf16) {
+          const u32x4 rr = *reinterpret_cast<const u32x4*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + n);
 #pragma unroll
-        for (int z = 0; z < 4; ++z) {
-          val[2 * z] += __uint_as_float(rr[z] << 16);
-          val[2 * z + 1] += __uint_as_float(rr[z] & 0xffff0000u);
+          for (int z = 0; z < 4; ++z) {
+            val[2 * z] += __uint_as_float(rr[z] << 16);
+            val[2 * z + 1] += __uint_as_float(rr[z] & 0xffff0000u);
+          }
         }
-      }
-      if (sg.resid_f32) {
-        const f32x4* rr = reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + n);
-        const f32x4 r0 = rr[0], r1 = rr[1];
+        if (sg.resid_f32) {
+          const f32x4* rr = reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + n);
+          const f32x4 r0 = rr[0], r1 = rr[1];
 #pragma unroll
-        for (int z = 0; z < 4; ++z) {
-          val[z] += r0[z];
-          val[4 + z] += r1[z];
+          for (int z = 0; z < 4; ++z) {
+            val[z] += r0[z];
+            val[4 + z] += r1[z];
+          }
         }
       }
       if (sg.out_f32) {
@@ -862,8 +907,10 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       load_input(L, sg, KT, NS, NCH, NBUF, nseq, 0);
       nseq += NCH;
       // ---- stage end: the LoRA wave has added the LoRA terms to the sums ---------------------------------------
+      float pre[8];
+      glue_prefetch(L, sg, NS, 0, pre);
       spin_until([&]() { return ld_lds(&c.tail_go) >= L + 1; });
-      glue(L, sg, NS, 0);
+      glue(L, sg, NS, 0, pre);
       wait_all_mem();
       st_lds(&c.tail_done, L + 1);
     }
@@ -952,6 +999,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         expand(L, sg, NS, NC, 0, npre, false);
         wave_sync();
       }
+      float pre[8];
+      glue_prefetch(L, sg, NS, 1, pre);
       // ---- stage end: all six stream waves have summed their part of the tiles ---------------------------------
       spin_until([&]() { return ld_lds(&c.sum_cnt) >= (L + 1) * kSW; });
       for (int m = lane; m < MT * 16; m += 64) {
@@ -973,7 +1022,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       if (cnt > npre) expand(L, sg, NS, NC, npre, cnt, true);
       wave_sync();
       st_lds(&c.tail_go, L + 1);
-      glue(L, sg, NS, 1);
+      glue(L, sg, NS, 1, pre);
       wait_all_mem();
       spin_until([&]() { return ld_lds(&c.tail_done) >= L + 1; });
       // `red` may be overwritten; the outputs of both waves are in memory: hand over to the stages that read them
