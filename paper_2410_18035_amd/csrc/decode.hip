@@ -65,6 +65,7 @@ struct Stage {
   int n_seg, pair, norm;
   int sync_before;  // the input is produced by earlier stages of this launch: wait for the grid barrier
   int lora_shrink;  // this stage starts the shrinks of its sites (first stage of a level)
+  int tpos0;        // shrink slot position of the level's first site (see shrink_slot)
   const bf16_t* W[3];
   int N[3], site[3];
   int unit0, units;  // this stage covers units [unit0, unit0 + units) of the level (tiles, or gate/up tile pairs),
@@ -87,12 +88,16 @@ struct Params {
   const uint8_t* route;
   const int32_t* row_to_req;
   int lora;
-  // LoRA shrinks, one slot per (row, site position inside its level): slot = row * 3 + position
+  // LoRA shrinks, one slot per (row, site position inside its level): see shrink_slot
   float* tpart;   // [slots][nc_max][r_max] shrink partials t = x[chunk] . A[chunk]
   float* tfin;    // [slots][r_max] t = x . A: the partials summed in chunk order by the wave that wrote the last one
   int* tcount;    // [slots] partials written so far in this launch; zero between launches
   int* tready;    // [slots] launch epoch * 16 + (stage that ran the shrink) + 1 of the t in tfin
   int nc_max;
+  float* wpart;   // wide kernel: [segments][tiles of a group][row tiles] partial tiles, 1 KiB each
+  float* wss;     // wide kernel: [segments][rows] sums of squares of the input rows over the segment
+  int* segflag;   // wide kernel: [segments] launch epoch * 16 + level of the segment stored there
+  int wsegs;      // wide kernel: segments per table half (even levels use the first half of the three tables, odd the second)
   int* flags;     // [kMaxGrid] grid barrier flags, monotone
   int* status;    // set to 1 when a bounded wait ran out
   Stage st[kMaxStages];
@@ -113,6 +118,10 @@ struct Ctrl {
   int tail_done;     // stages whose outputs the loader wave has stored
   int epoch;
   int l_cnt;
+  int seg_arr[8];  // wide kernel: stream waves that have stored their part of a segment (segment number % 8)
+  int lvl_arr[kMaxStages];  // wide kernel: waves that have finished the level (a wave with nothing to do in a level runs ahead)
+  int shr_next[kMaxStages];  // wide kernel: shrink items of a level handed out so far (the LoRA and loader waves draw from it)
+  int shr_ready;   // wide kernel: levels whose shrink list stands in s_rows
   int s_flag;
   float ss_part[kSW][kMaxRows];
   float inv_rows[kMaxRows];
@@ -124,6 +133,13 @@ struct Ctrl {
   int s_cnt;
 };
 static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
+
+// Shrink slot of (row, site position inside the level).  A row has kSlotsPerRow slots: q,k,v and gate,up use positions
+// 0..2, o and down position 3 - levels that reuse a position are always separated by a grid barrier, while o can
+// follow q,k,v without one (attention output supplied by the caller), and with several sites per request a row
+// can have a LoRA term in both.
+constexpr int kSlotsPerRow = 4;
+__device__ __host__ __forceinline__ int shrink_slot(const Stage& sg, int m, int pos) { return m * kSlotsPerRow + sg.tpos0 + pos; }
 
 // ---- memory-model helpers ---------------------------------------------------------------------------
 __device__ __forceinline__ int ld_agent(const int* p) {
@@ -223,7 +239,7 @@ __device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, i
 template <int MT>
 __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& sg, int m, int pos, int tenant, int r,
                                                  int kc, int NC, int tag, int lane) {
-  const int site = sg.site[pos], slot = m * 3 + pos;
+  const int site = sg.site[pos], slot = shrink_slot(sg, m, pos);
   const gbf16* A = (const gbf16*)p.ad.A[tenant * MILORA_NUM_SITES + site];
   const int K = sg.K, rmax = p.ad.r_max;
   const int k_lo = kc * kShrinkChunk;
@@ -655,8 +671,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   };
   // LoRA expand of list entries [l0, l1): lane = (entry, tile, column quad); added to `red` or stored in `delta`
   // shrink t[c] of row m, as published by the wave that summed the row's partials
-  auto t_sum = [&](int m, int s, int c) __attribute__((always_inline)) -> float {
-    return ld_agent(p.tfin + (size_t)(m * 3 + s) * p.ad.r_max + c);
+  auto t_sum = [&](const Stage& sg, int m, int s, int c) __attribute__((always_inline)) -> float {
+    return ld_agent(p.tfin + (size_t)shrink_slot(sg, m, s) * p.ad.r_max + c);
   };
   auto expand = [&](const int L, const Stage& sg, const int NS, const int NC, int l0, int l1, bool to_red) __attribute__((always_inline)) {
     const int work = (l1 - l0) * NS * 4;
@@ -680,7 +696,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
               bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(cc + u) * ldb);
-              t[u] = to_red ? t_sum(m, s, cc + u) : tv[cc + u];
+              t[u] = to_red ? t_sum(sg, m, s, cc + u) : tv[cc + u];
             }
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
@@ -692,7 +708,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
           }
           for (; cc < r; ++cc) {
             const u32x2 bb = *reinterpret_cast<const gu32x2*>(Bm + (size_t)cc * ldb);
-            const float t = to_red ? t_sum(m, s, cc) : tv[cc];
+            const float t = to_red ? t_sum(sg, m, s, cc) : tv[cc];
             d[0] += t * __uint_as_float(bb[0] << 16);
             d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
             d[2] += t * __uint_as_float(bb[1] << 16);
@@ -700,7 +716,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
           }
         } else {
           for (int cc = 0; cc < r; ++cc) {
-            const float t = to_red ? t_sum(m, s, cc) : tv[cc];
+            const float t = to_red ? t_sum(sg, m, s, cc) : tv[cc];
 #pragma unroll
             for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)cc * ldb + z]);
           }
@@ -980,7 +996,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
           int spins = 0;
           for (int e = lane; e < ((cnt + 63) & ~63); e += 64) {
             const int ms = c.l_ms[e < cnt ? e : 0];
-            const int* f = p.tready + (ms & 0xff) * 3 + (ms >> 8);
+            const int* f = p.tready + shrink_slot(sg, ms & 0xff, ms >> 8);
             while (!__all(e >= cnt || ld_agent(f) == lvl_tag)) {
               if (++spins >= kSpinLimit) { *p.status = 1; break; }
               __builtin_amdgcn_s_sleep(2);
@@ -993,7 +1009,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         for (int e = lane; e < npre * p.ad.r_max; e += 64) {
           const int li = e / p.ad.r_max, cc = e - li * p.ad.r_max;
           const int ms = c.l_ms[li];
-          t_lds[e] = cc < c.r_rank[ms & 0xff] ? t_sum(ms & 0xff, ms >> 8, cc) : 0.f;
+          t_lds[e] = cc < c.r_rank[ms & 0xff] ? t_sum(sg, ms & 0xff, ms >> 8, cc) : 0.f;
         }
         wave_sync();
         expand(L, sg, NS, NC, 0, npre, false);
@@ -1046,6 +1062,509 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const u32x4* __restric
   dst[g] = src[((size_t)jrow * d1 + i0) / 8];
 }
 
+// =====================================================================================================================
+// Wide batches (65..128 rows; the code also serves 33..64, where it is no faster than the stream kernel).  With this many rows the stage input is as large as a workgroup's share of the weights,
+// and a workgroup that owns a few 16-column tiles over the whole reduction reads all of it: the input copies, not the
+// weights, set the time.  Here a level (q,k,v | o | gate,up | down) is cut the other way: a group is kSW * TPW tiles
+// wide (each stream wave holds TPW tiles of it, over all rows), the (group, k block) space of a level is laid out in a
+// line and dealt to the workgroups in equal contiguous pieces, so a workgroup reads only its piece of the reduction
+// of the input.  A piece that ends inside a group leaves a segment: its fp32 partial tiles go to memory, and when all
+// segments of a group are there, the group's tiles are summed in segment order, get their LoRA term and the level's
+// glue, and are stored - each (tile, row tile) by one wave of the workgroup it is dealt to.
+// =====================================================================================================================
+template <int MT> struct WCfg;
+template <> struct WCfg<4> { static constexpr int TPW = 4, D = 4, CKB = 4; };
+template <> struct WCfg<8> { static constexpr int TPW = 2, D = 6, CKB = 2; };
+constexpr int kWideGridMax = 256;   // workgroups the segment tables are sized for
+
+__device__ __forceinline__ void st_through(u32x2* p, u32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+}
+// Four 16-byte loads that bypass the caches (the partial tiles are written by other workgroups in this launch, into
+// memory that earlier levels and launches have used), complete when the function returns.
+__device__ __forceinline__ void ld_through4(const f32x4* p0, const f32x4* p1, const f32x4* p2, const f32x4* p3, f32x4 (&v)[4]) {
+  asm volatile(
+      "global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
+      "global_load_dwordx4 %1, %5, off sc0 sc1\n\t"
+      "global_load_dwordx4 %2, %6, off sc0 sc1\n\t"
+      "global_load_dwordx4 %3, %7, off sc0 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+      : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+      : "memory");
+}
+
+// units (tiles, or gate/up tile pairs) and groups of a level
+__device__ __host__ __forceinline__ int wide_units(const Stage& s) {
+  if (s.pair) return s.N[0] >> 4;
+  int t = 0;
+  for (int i = 0; i < s.n_seg; ++i) t += s.N[i] >> 4;
+  return t;
+}
+__device__ __host__ __forceinline__ int wide_groups(const Stage& s, int NT) {
+  const int upg = s.pair ? NT / 2 : NT;
+  return (wide_units(s) + upg - 1) / upg;
+}
+
+template <int MT>
+__global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
+  constexpr int TPW = WCfg<MT>::TPW, D = WCfg<MT>::D, CKB = WCfg<MT>::CKB, NT = kSW * TPW;
+  constexpr int kChunk = CKB * MT * 1024;                         // bytes of an input chunk: CKB k blocks, all rows
+  constexpr int NBUF = (kLdsBytes - kCtrlBytes) / kChunk;         // chunk buffers
+  constexpr int LPC = CKB * MT;                                   // wave loads per chunk
+  constexpr int kDepth = (63 / LPC + 1) < NBUF ? (63 / LPC + 1) : NBUF;  // chunks the loader keeps in flight
+  static_assert(D % CKB == 0 && LPC <= 63 && NBUF >= 4, "chunks");
+  extern __shared__ __align__(16) unsigned char smem[];
+  Ctrl& c = *reinterpret_cast<Ctrl*>(smem);
+  unsigned char* const xreg = smem + kCtrlBytes;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wg = blockIdx.x, G = gridDim.x;
+
+  if (tid == 0) {
+    c.x_ready[0] = 0;
+    c.shr_ready = 0;
+    c.epoch = (ld_agent(p.flags + wg) >> 4) + 1;
+  }
+  if (tid < 8) {
+    c.x_done[tid] = 0;
+    c.seg_arr[tid] = 0;
+  }
+  if (tid < kMaxStages) { c.shr_next[tid] = 0; c.lvl_arr[tid] = 0; }
+  if (tid >= 64 && tid < 64 + kMaxRows) {
+    const int m = tid - 64;
+    int mask = 0, tenant = 0, r = 0;
+    if (m < p.M && p.lora) {
+      const int req = p.row_to_req ? p.row_to_req[m] : m;
+      if (req >= 0 && req < p.Breq) {
+        const uint8_t rb = p.route[req];
+        for (int st = 0; st < MILORA_NUM_SITES; ++st)
+          if (route_has(rb, st)) {
+            r = routed_rank(p.ad, p.tenant_id, p.route, req, p.Breq, st, &tenant);  // the same for every chosen site
+            if (r > 0) mask |= 1 << st;
+          }
+      }
+    }
+    c.r_mask[m] = mask;
+    c.r_ten[m] = tenant;
+    c.r_rank[m] = r;
+  }
+  __syncthreads();
+  const int epoch = __builtin_amdgcn_readfirstlane(c.epoch);
+
+  auto spin_until = [&](auto cond) __attribute__((always_inline)) {
+    int spins = 0;
+    while (!cond()) {
+      if (++spins >= kSpinLimit) { *p.status = 1; break; }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    compiler_fence();
+  };
+  auto wave_sync = [&]() __attribute__((always_inline)) {
+    compiler_fence();
+    wait_lds();
+    compiler_fence();
+  };
+
+  // The level's shrink items (row with a LoRA term at a site of the level, k chunk) are spread over the grid; those
+  // of this workgroup are drawn one by one by its LoRA wave and, once its copies are out, its loader wave.
+  auto shrink_items = [&](const int L, const Stage& sg) __attribute__((always_inline)) {
+    const int NC = shrink_chunks(sg.K);
+    const int items = ld_lds(&c.s_cnt) * NC;
+    for (;;) {
+      int k = 0;
+      if (lane == 0) k = __hip_atomic_fetch_add(&c.shr_next[L], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      k = __builtin_amdgcn_readfirstlane(k);
+      const long it = (long)((wg + 97 * L) % G) + (long)k * G;
+      if (it >= items) break;
+      const int ms = c.s_rows[it / NC], m = ms & 0xff;
+      lora_shrink_item<MT>(p, sg, m, ms >> 8, c.r_ten[m], c.r_rank[m], (int)(it % NC), NC, epoch * 16 + L + 1, lane);
+    }
+  };
+
+  int xs = 0;      // input chunks of the segments so far (the same count in every wave)
+  int segord = 0;  // segments so far
+  int seen = 0;    // stream waves: chunks known to have landed
+
+  for (int L = 0; L < p.n_stages; ++L) {
+    const Stage& sg = p.st[L];
+    const int KT = sg.K >> 5;
+    const int T = wide_units(sg), upg = sg.pair ? NT / 2 : NT, groups = (T + upg - 1) / upg;
+    const long Wt = (long)groups * KT;
+    const int act = Wt < (long)G ? (int)Wt : G;  // workgroups that get a piece of the level
+    const int tag = epoch * 16 + L;
+    // Segment tables of even and odd levels lie apart: a level that follows another without a barrier (o after q,k,v
+    // when the caller supplies the attention output) must not touch what that one's sums still read.
+    const int sbase = (L & 1) * p.wsegs;
+    // the workgroup that owns position x of the line: the last one whose piece starts at or before x
+    auto owner = [&](long x) __attribute__((always_inline)) -> int { return (int)(((x + 1) * act - 1) / Wt); };
+    long lo = 0, hi = 0;
+    if (wg < act) {
+      lo = (long)wg * Wt / act;
+      hi = (long)(wg + 1) * Wt / act;
+    }
+    // the tiles this workgroup sums and stores: consecutive ones (they lie in one group, two at most)
+    const int tpg = (T + G - 1) / G;
+    const int t0 = wg * tpg < T ? wg * tpg : T, t1 = t0 + tpg < T ? t0 + tpg : T;
+    const int lvl_tag = epoch * 16 + L + 1;
+    // unit (tile, or gate/up pair) -> site position and tile inside the site's matrix
+    auto unit_tile = [&](int ti, int& sp) __attribute__((always_inline)) -> int {
+      sp = 0;
+      if (sg.pair) return ti;
+      int u = ti;
+      while (sp + 1 < sg.n_seg && u >= (sg.N[sp] >> 4)) {
+        u -= sg.N[sp] >> 4;
+        ++sp;
+      }
+      return u;
+    };
+    // LoRA term of row m at site position sp for the four columns from ncol on; the row's shrink is published
+    auto lora_quad = [&](const int m, const int sp, const int ncol, float (&d)[4]) __attribute__((always_inline)) {
+      const int r = c.r_rank[m];
+      const size_t ldb = (size_t)sg.N[sp];
+      const gbf16* Bm = (const gbf16*)p.ad.B[c.r_ten[m] * MILORA_NUM_SITES + sg.site[sp]] + ncol;
+      const float* tf = p.tfin + (size_t)shrink_slot(sg, m, sp) * p.ad.r_max;
+      if (((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0) {
+        int cc = 0;
+        for (; cc + 16 <= r; cc += 16) {
+          u32x2 bb[16];
+          float t[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) {
+            bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(cc + u) * ldb);
+            t[u] = ld_agent(tf + cc + u);
+          }
+#pragma unroll
+          for (int u = 0; u < 16; ++u) {
+            d[0] += t[u] * __uint_as_float(bb[u][0] << 16);
+            d[1] += t[u] * __uint_as_float(bb[u][0] & 0xffff0000u);
+            d[2] += t[u] * __uint_as_float(bb[u][1] << 16);
+            d[3] += t[u] * __uint_as_float(bb[u][1] & 0xffff0000u);
+          }
+        }
+        for (; cc < r; ++cc) {
+          const u32x2 bb = *reinterpret_cast<const gu32x2*>(Bm + (size_t)cc * ldb);
+          const float t = ld_agent(tf + cc);
+          d[0] += t * __uint_as_float(bb[0] << 16);
+          d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
+          d[2] += t * __uint_as_float(bb[1] << 16);
+          d[3] += t * __uint_as_float(bb[1] & 0xffff0000u);
+        }
+      } else {
+        for (int cc = 0; cc < r; ++cc) {
+          const float t = ld_agent(tf + cc);
+#pragma unroll
+          for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)cc * ldb + z]);
+        }
+      }
+    };
+
+    if (w < kSW) {
+      // ===================================== stream waves =====================================
+      const int rd_off = sg.x_packed ? lane * 16 : ((lane & 15) * 4 + (lane >> 4)) * 16;
+      const bool norm = sg.norm != 0;
+      for (long pos = lo; pos < hi;) {
+        const int g = (int)(pos / KT), kb0 = (int)(pos - (long)g * KT);
+        const long gend = (long)(g + 1) * KT;
+        const int len = (int)((hi < gend ? hi : gend) - pos);
+        const int sid = sbase + wg + g;
+        const int nch = (len + CKB - 1) / CKB;
+        // this wave's tiles of the group
+        const gu32x4* wp[TPW];
+        bool tval[TPW];
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+          int seg = 0, tile;
+          if (sg.pair) {
+            tile = g * upg + w * (TPW / 2) + (j >> 1);
+            seg = j & 1;
+            tval[j] = tile < T;
+          } else {
+            int u = g * NT + w * TPW + j;
+            tval[j] = u < T;
+            if (!tval[j]) u = 0;
+            while (seg + 1 < sg.n_seg && u >= (sg.N[seg] >> 4)) {
+              u -= sg.N[seg] >> 4;
+              ++seg;
+            }
+            tile = u;
+          }
+          if (!tval[j]) { seg = 0; tile = 0; }  // streams valid memory, result dropped
+          wp[j] = (const gu32x4*)sg.W[seg] + ((size_t)tile * KT + kb0) * 64 + lane;
+        }
+        u32x4 ring[D][TPW];
+        f32x4 acc[TPW][MT];
+#pragma unroll
+        for (int j = 0; j < TPW; ++j)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[j][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float ss[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) ss[mt] = 0.f;
+#pragma unroll
+        for (int s = 0; s < D; ++s)
+#pragma unroll
+          for (int j = 0; j < TPW; ++j) ring[s][j] = __builtin_nontemporal_load(wp[j] + (size_t)(s < len ? s : len - 1) * 64);
+        for (int i0 = 0; i0 < len; i0 += D) {
+#pragma unroll
+          for (int s = 0; s < D; ++s) {
+            const int i = i0 + s;
+            const bool valid = i < len;
+            if (s % CKB == 0) {
+              // next chunk: the ones before it are consumed; it has landed
+              const int chn = i / CKB;
+              compiler_fence();
+              st_lds(&c.x_done[w], xs + (chn < nch ? chn : nch));
+              if (valid && seen <= xs + chn) spin_until([&]() { return (seen = ld_lds(&c.x_ready[0])) > xs + chn; });
+            }
+            const uint32_t mask = valid ? 0xffffffffu : 0u;
+            const int chn = valid ? i / CKB : nch - 1;
+            const unsigned char* xbuf = xreg + ((xs + chn) % NBUF) * kChunk + (s % CKB) * (MT * 1024) + rd_off;
+            u32x4 xb[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xb[mt] = *reinterpret_cast<const u32x4*>(xbuf + mt * 1024) & mask;
+            if (norm && w == 0) {
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) ss[mt] += sumsq8(xb[mt]);
+            }
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) {
+              const u32x4 wv = ring[s][j] & mask;
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt)
+                acc[j][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv), __builtin_bit_cast(bf16x8, xb[mt]),
+                                                                    acc[j][mt], 0, 0, 0);
+            }
+            const int nx = i + D < len ? i + D : len - 1;
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) ring[s][j] = __builtin_nontemporal_load(wp[j] + (size_t)nx * 64);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        compiler_fence();
+        st_lds(&c.x_done[w], xs + nch);
+        // the segment's partial tiles, as the matrix cores leave them: lane = (row lane % 16, columns 4 (lane / 16) ..)
+        f32x4* const P = reinterpret_cast<f32x4*>(p.wpart) + ((size_t)sid * NT + w * TPW) * (MT * 64) + lane;
+#pragma unroll
+        for (int j = 0; j < TPW; ++j)
+          if (tval[j])
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) st_through(P + (j * MT + mt) * 64, acc[j][mt]);
+        if (norm && w == 0) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            float v = ss[mt];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (lane < 16) st_agent(p.wss + (size_t)sid * (MT * 16) + mt * 16 + lane, v);
+          }
+        }
+        wait_all_mem();
+        // the last of the six waves announces the segment
+        int old = 0;
+        if (lane == 0) old = __hip_atomic_fetch_add(&c.seg_arr[segord & 7], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        old = __builtin_amdgcn_readfirstlane(old);
+        if (old + 1 == kSW * ((segord >> 3) + 1) && lane == 0) st_agent(p.segflag + sid, tag);
+        xs += nch;
+        ++segord;
+        pos += len;
+      }
+    } else if (w == kLoader) {
+      // ===================================== input loader =====================================
+      if (sg.sync_before && L > 0) {
+        if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) {
+          *p.status = 1;
+        }
+      }
+      const unsigned char* const Xb = reinterpret_cast<const unsigned char*>(sg.X);
+      const bool xpk = sg.x_packed != 0;
+      size_t loff[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        int row = mt * 16 + (lane >> 2);
+        if (row > p.M - 1) row = p.M - 1;
+        loff[mt] = xpk ? (size_t)mt * 1024 + lane * 16 : ((size_t)row * sg.ldx + (lane & 3) * 8) * sizeof(bf16_t);
+      }
+      const size_t kstep = xpk ? (size_t)MT * 1024 : 64;
+      const uint32_t done_off = lds_off(&c.x_done[lane < kSW ? lane : 0]), ready_off = lds_off(&c.x_ready[0]);
+      int issued = 0;  // chunks of this level
+      for (long pos = lo; pos < hi;) {
+        const int g = (int)(pos / KT), kb0 = (int)(pos - (long)g * KT);
+        const long gend = (long)(g + 1) * KT;
+        const int len = (int)((hi < gend ? hi : gend) - pos);
+        const int nch = (len + CKB - 1) / CKB;
+        for (int ch = 0; ch < nch; ++ch) {
+          const int n = xs + issued;  // this chunk's number; it reuses the buffer of chunk n - NBUF
+          spin_until([&]() { return __all(lds_peek(done_off) >= n - NBUF + 1); });
+          unsigned char* const dst = xreg + (n % NBUF) * kChunk;
+#pragma unroll
+          for (int kk = 0; kk < CKB; ++kk) {
+            int kb = ch * CKB + kk;
+            kb = kb0 + (kb < len ? kb : len - 1);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xb + (size_t)kb * kstep + loff[mt]),
+                                               (__attribute__((address_space(3))) void*)(dst + ((kk * MT + mt) << 10)), 16, 0, 0);
+          }
+          ++issued;
+          if (issued >= kDepth) {
+            wait_vm<LPC * (kDepth - 1)>();
+            lds_poke(ready_off, xs + issued - kDepth + 1);
+          }
+        }
+        pos += len;
+      }
+      wait_vm<0>();
+      lds_poke(ready_off, xs + issued);
+      xs += issued;
+      if (p.lora) {  // the copies are out: help with the level's shrinks
+        spin_until([&]() { return ld_lds(&c.shr_ready) >= L + 1; });
+        shrink_items(L, sg);
+      }
+    } else {
+      // ===================================== LoRA wave: the level's shrinks =====================================
+      if (p.lora) {
+        if (sg.sync_before && L > 0) {
+          if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) {
+            *p.status = 1;
+          }
+        }
+        // the level's rows with a LoRA term, in row order (the same list in every workgroup); the loader wave may
+        // still be drawing the previous level's items from the list when this level has no barrier before it
+        if (L > 0) spin_until([&]() { return ld_lds(&c.lvl_arr[L - 1]) >= kWaves; });
+        if (lane == 0) c.s_cnt = 0;
+        wave_sync();
+        for (int s = 0; s < sg.n_seg; ++s)
+          for (int m0 = 0; m0 < p.M; m0 += 64) {
+            const int m = m0 + lane;
+            const bool has = m < p.M && ((c.r_mask[m < p.M ? m : 0] >> sg.site[s]) & 1);
+            const unsigned long long mask = __ballot(has);
+            const int base = c.s_cnt;
+            if (has) c.s_rows[base + __popcll(mask & ((1ull << lane) - 1ull))] = m | (s << 8);
+            wave_sync();
+            if (lane == 0) c.s_cnt = base + __popcll(mask);
+            wave_sync();
+          }
+        if (lane == 0) st_lds(&c.shr_ready, L + 1);
+        shrink_items(L, sg);
+      }
+    }
+    // ===================================== all waves: sum, LoRA term, glue, store =====================================
+    {
+      int uc = 0;
+      for (int ti = t0; ti < t1; ++ti)
+        for (int mt = 0; mt < MT; ++mt, ++uc) {
+          if ((uc & 7) != w) continue;
+          int s;
+          const int tile = unit_tile(ti, s);
+          int g, a0;
+          if (sg.pair) {
+            g = ti / upg;
+            const int pi = ti - g * upg;
+            a0 = (pi / (TPW / 2)) * TPW + 2 * (pi % (TPW / 2));
+          } else {
+            g = ti / NT;
+            a0 = ti - g * NT;
+          }
+          const long x0 = (long)g * KT;
+          const int wf = owner(x0), wl = owner(x0 + KT - 1), n = wl - wf + 1, sid0 = sbase + wf + g;
+          const int m = mt * 16 + (lane & 15), q = lane >> 4;
+          const int ncol = tile * 16 + q * 4;
+          // LoRA term of this lane's row and four columns at site position sp
+          auto lora_term = [&](const int sp, float (&d)[4]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int z = 0; z < 4; ++z) d[z] = 0.f;
+            const bool has = p.lora && m < p.M && ((c.r_mask[m < p.M ? m : 0] >> sg.site[sp]) & 1);
+            const int* f = p.tready + shrink_slot(sg, m < p.M ? m : 0, sp);
+            spin_until([&]() { return __all(!has || ld_agent(f) == lvl_tag); });
+            if (has) lora_quad(m, sp, ncol, d);
+          };
+          float da[4], db[4];
+          lora_term(s, da);
+          if (sg.pair) lora_term(1, db);
+          // the group's segments are there
+          for (int b = 0; b < n; b += 64) {
+            const int i = b + lane;
+            const int* f = p.segflag + sid0 + (i < n ? i : 0);
+            spin_until([&]() { return __all(i >= n || ld_agent(f) == tag); });
+          }
+          f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+          float ssq = 0.f;
+          if (sg.norm) {  // lane = (row, segment % 4): the segments' sums of squares in one round trip
+            for (int b = 0; b < n; b += 4) {
+              const int i = b + q;
+              if (i < n) ssq += ld_agent(p.wss + (size_t)(sid0 + i) * (MT * 16) + m);
+            }
+          }
+          const size_t sstride = (size_t)NT * MT * 64;
+          const f32x4* const P0 = reinterpret_cast<const f32x4*>(p.wpart) + ((size_t)sid0 * NT + a0) * (MT * 64) + mt * 64 + lane;
+          for (int i = 0; i < n; i += 4) {
+            f32x4 v[4];
+            const int i1 = i + 1 < n ? i + 1 : n - 1, i2 = i + 2 < n ? i + 2 : n - 1, i3 = i + 3 < n ? i + 3 : n - 1;
+            ld_through4(P0 + i * sstride, P0 + i1 * sstride, P0 + i2 * sstride, P0 + i3 * sstride, v);
+            sa += v[0];
+            if (i + 1 < n) sa += v[1];
+            if (i + 2 < n) sa += v[2];
+            if (i + 3 < n) sa += v[3];
+            if (sg.pair) {
+              const f32x4* const P1 = P0 + MT * 64;
+              ld_through4(P1 + i * sstride, P1 + i1 * sstride, P1 + i2 * sstride, P1 + i3 * sstride, v);
+              sb += v[0];
+              if (i + 1 < n) sb += v[1];
+              if (i + 2 < n) sb += v[2];
+              if (i + 3 < n) sb += v[3];
+            }
+          }
+          if (sg.norm) {
+            ssq += __shfl_xor(ssq, 16, 64);
+            ssq += __shfl_xor(ssq, 32, 64);
+          }
+          if (m < p.M) {
+            const float inv = sg.norm ? rsqrtf(ssq / (float)sg.K + 1e-5f) : 1.f;
+            float val[4];
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+              const float v0 = (sa[z] + da[z]) * inv;
+              val[z] = sg.pair ? silu(v0) * ((sb[z] + db[z]) * inv) : v0;
+            }
+            if (sg.bias[s]) {
+              const u32x2 bb = *reinterpret_cast<const u32x2*>(sg.bias[s] + ncol);
+              val[0] += __uint_as_float(bb[0] << 16);
+              val[1] += __uint_as_float(bb[0] & 0xffff0000u);
+              val[2] += __uint_as_float(bb[1] << 16);
+              val[3] += __uint_as_float(bb[1] & 0xffff0000u);
+            }
+            if (sg.resid_bf16) {
+              const u32x2 rr = *reinterpret_cast<const u32x2*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + ncol);
+              val[0] += __uint_as_float(rr[0] << 16);
+              val[1] += __uint_as_float(rr[0] & 0xffff0000u);
+              val[2] += __uint_as_float(rr[1] << 16);
+              val[3] += __uint_as_float(rr[1] & 0xffff0000u);
+            }
+            if (sg.resid_f32) {
+              const f32x4 rr = *reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + ncol);
+#pragma unroll
+              for (int z = 0; z < 4; ++z) val[z] += rr[z];
+            }
+            if (sg.out_f32) st_through(reinterpret_cast<f32x4*>(sg.out_f32 + (size_t)m * sg.ld_f32 + ncol), f32x4{val[0], val[1], val[2], val[3]});
+            const u32x2 o = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
+            if (sg.out[s]) *reinterpret_cast<u32x2*>(sg.out[s] + (size_t)m * sg.ld_out[s] + ncol) = o;
+            if (sg.out_pk && (sg.pair || s == sg.n_seg - 1)) st_through(reinterpret_cast<u32x2*>(sg.out_pk + packed_x_offset(m, ncol, MT)), o);
+          }
+        }
+    }
+    // ---- level end: the last wave to get here hands the level over ----
+    wait_all_mem();
+    {
+      int old = 0;
+      if (lane == 0) old = __hip_atomic_fetch_add(&c.lvl_arr[L], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      old = __builtin_amdgcn_readfirstlane(old);
+      if (old + 1 == kWaves && lane == 0) st_agent(p.flags + wg, epoch * 16 + (L + 1 < p.n_stages ? L + 1 : 15));
+    }
+  }
+}
+
 int mt_for(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : (M <= 64 ? 4 : 8)); }
 int ns_max_for(int MT) { return MT <= 2 ? Cfg<2>::NS : (MT == 4 ? Cfg<4>::NS : Cfg<8>::NS); }
 
@@ -1087,8 +1606,34 @@ int launch_stream(const Params& p, int MT, int G, hipStream_t st) {
   return check_launch();
 }
 
+// The wide kernel's grid: one workgroup per compute unit, at most as many as the segment tables hold.
+template <int MT>
+int wide_grid() {
+  static int cached = 0;
+  if (cached) return cached;
+  int dev = 0, cus = 0, occ = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_wide_kernel<MT>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kLdsBytes) != hipSuccess)
+    return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_wide_kernel<MT>, kThreads, kLdsBytes) != hipSuccess) return 0;
+  if (occ < 1 || cus < 1) return 0;
+  cached = cus > kWideGridMax ? kWideGridMax : cus;
+  return cached;
+}
+
+int wide_tiles_per_group(int MT) { return kSW * (MT == 4 ? WCfg<4>::TPW : WCfg<8>::TPW); }
+
+// Segments a launch can leave: every workgroup's piece ends one, and so does every group.
+int wide_segments(int MT, int d, int F) {
+  const int NT = wide_tiles_per_group(MT);
+  const int g_qkv = (3 * (d >> 4) + NT - 1) / NT, g_gu = ((F >> 4) + NT / 2 - 1) / (NT / 2);
+  return kWideGridMax + (g_qkv > g_gu ? g_qkv : g_gu);
+}
+
 void reset_stage(Stage& s) {
-  s.X = nullptr; s.ldx = 0; s.K = 0; s.x_packed = 0; s.out_pk = nullptr; s.n_seg = 0; s.pair = 0; s.norm = 0; s.sync_before = 0; s.lora_shrink = 0;
+  s.X = nullptr; s.ldx = 0; s.K = 0; s.x_packed = 0; s.out_pk = nullptr; s.n_seg = 0; s.pair = 0; s.norm = 0; s.sync_before = 0; s.lora_shrink = 0; s.tpos0 = 0;
   s.unit0 = 0; s.units = 0; s.cap = 1;
   for (int i = 0; i < 3; ++i) {
     s.W[i] = nullptr; s.N[i] = 0; s.site[i] = -1; s.bias[i] = nullptr; s.out[i] = nullptr; s.ld_out[i] = 0;
@@ -1147,34 +1692,44 @@ bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_ma
 struct DecodeWs {
   int* flags;      // [kMaxGrid] barrier flags; zero before the first launch, then owned by the kernels
   int* status;
-  int* tready;     // [3 kMaxRows] per shrink slot: epoch of the launch that published it
-  int* tcount;     // [3 kMaxRows] partials written so far (zero between launches)
-  float* tfin;     // [3 M][r_max] published shrinks
-  float* tpart;    // [3 M][NCmax][r_max] shrink partials
+  int* tready;     // [kSlotsPerRow kMaxRows] per shrink slot: epoch of the launch that published it
+  int* tcount;     // [kSlotsPerRow kMaxRows] partials written so far (zero between launches)
+  float* tfin;     // [kSlotsPerRow M][r_max] published shrinks
+  float* tpart;    // [kSlotsPerRow M][NCmax][r_max] shrink partials
   float* h_f32;    // [M][d]
   bf16_t* v_pk;    // a = v as operand blocks   (K = d)
   bf16_t* h_pk;    // h as operand blocks       (K = d)
   bf16_t* m_pk;    // m = silu(g) * u as operand blocks (K = F)
+  int* segflag;    // wide kernel, layer decode of more than 64 rows only: see Params
+  float* wss;
+  float* wpart;
   size_t bytes;
 };
 
-DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max) {
+DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max, bool wide = false) {
   const int big = F > d ? F : d;
   size_t off = 0;
   auto take = [&](size_t n) { size_t o = off; off += align_up(n, 256); return o; };
   const size_t o_fl = take((size_t)(kMaxGrid + 64) * sizeof(int));
-  const size_t o_p = take((size_t)kMaxRows * 6 * sizeof(int));  // at a fixed place whatever M is: the counters must read zero
-  const size_t o_tf = take((size_t)3 * M * r_max * sizeof(float));
-  const size_t o_t = take((size_t)3 * M * shrink_chunks(big) * r_max * sizeof(float));
+  const size_t o_p = take((size_t)kMaxRows * 2 * kSlotsPerRow * sizeof(int));  // at a fixed place whatever M is: the counters must read zero
+  const size_t o_tf = take((size_t)kSlotsPerRow * M * r_max * sizeof(float));
+  const size_t o_t = take((size_t)kSlotsPerRow * M * shrink_chunks(big) * r_max * sizeof(float));
   const size_t o_h = take((size_t)M * d * sizeof(float));
   const int rows = mt_for(M) * 16;
   const size_t o_v = take((size_t)rows * d * sizeof(bf16_t));
   const size_t o_hb = take((size_t)rows * d * sizeof(bf16_t));
   const size_t o_m = take((size_t)rows * F * sizeof(bf16_t));
+  size_t o_sf = 0, o_ss = 0, o_wp = 0;
+  if (wide) {
+    const int MT = mt_for(M), segs = 2 * wide_segments(MT, d, F);
+    o_sf = take((size_t)segs * sizeof(int));
+    o_ss = take((size_t)segs * rows * sizeof(float));
+    o_wp = take((size_t)segs * wide_tiles_per_group(MT) * MT * 1024);
+  }
   char* b = (char*)base;
   int* fl = (int*)(b + o_fl);
-  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (int*)(b + o_p) + 3 * kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
-                  (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb), (bf16_t*)(b + o_m), off};
+  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (int*)(b + o_p) + kSlotsPerRow * kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
+                  (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb), (bf16_t*)(b + o_m), (int*)(b + o_sf), (float*)(b + o_ss), (float*)(b + o_wp), off};
 }
 
 void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const AdapterView& ad, const int32_t* tenant_id,
@@ -1183,11 +1738,12 @@ void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const
   p.lora = 1;
   p.tpart = ws.tpart; p.tfin = ws.tfin; p.tcount = ws.tcount; p.tready = ws.tready; p.nc_max = shrink_chunks(Kmax);
   p.flags = ws.flags; p.status = ws.status;
+  p.wpart = ws.wpart; p.wss = ws.wss; p.segflag = ws.segflag; p.wsegs = 0;
 }
 
 }  // namespace
 
-size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max) { return carve_decode_ws(nullptr, M, d, F, r_max).bytes; }
+size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max) { return carve_decode_ws(nullptr, M, d, F, r_max, M > 64).bytes; }
 
 // The word the stream kernels set when one of their bounded waits ran out (it lies at the same place in every
 // workspace of the packed paths).  Waits for the stream's work, then copies the word to the host.
@@ -1204,46 +1760,78 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
                         const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
                         bf16_t* y, bf16_t* qkv_out, void* workspace, hipStream_t st, LaunchMarks* marks) {
   const int MT = mt_for(B);
-  const int G = grid_for(MT);
+  const bool wide = MT >= 8;  // more than 64 rows: the kernel that cuts the reduction over the workgroups
+  const int G = wide ? (MT == 4 ? wide_grid<4>() : wide_grid<8>()) : grid_for(MT);
   if (G <= 0) return hip_fail(hipGetLastError());
   const int nsm = ns_max_for(MT);
-  DecodeWs ws = carve_decode_ws(workspace, B, d, F, ad.r_max);
+  DecodeWs ws = carve_decode_ws(workspace, B, d, F, ad.r_max, B > 64);
   const int norm = (flags & MILORA_LAYER_RMSNORM) ? 1 : 0;
   Params p;
   fill_common(p, ws, B, B, F > d ? F : d, ad, tenant_id, route, nullptr);
-  Stage l;
+  Stage lv[4];
+  int units[4];
   // level 0: q, k, v from x
-  reset_stage(l);
-  l.X = x; l.ldx = d; l.K = d; l.n_seg = 3; l.norm = norm;
-  for (int s = 0; s < 3; ++s) {
-    l.W[s] = (const bf16_t*)wts->W[s]; l.N[s] = d; l.site[s] = s;
-    if (qkv_out) { l.out[s] = qkv_out + (size_t)s * d; l.ld_out[s] = 3 * d; }
+  {
+    Stage& l = lv[0];
+    reset_stage(l);
+    l.X = x; l.ldx = d; l.K = d; l.n_seg = 3; l.norm = norm;
+    for (int s = 0; s < 3; ++s) {
+      l.W[s] = (const bf16_t*)wts->W[s]; l.N[s] = d; l.site[s] = s;
+      if (qkv_out) { l.out[s] = qkv_out + (size_t)s * d; l.ld_out[s] = 3 * d; }
+    }
+    if (!attn_out) l.out_pk = ws.v_pk;  // a = v goes to the next stage as operand blocks
+    units[0] = 3 * (d >> 4);
   }
-  if (!attn_out) l.out_pk = ws.v_pk;  // a = v goes to the next stage as operand blocks
-  if (!push_level(p, l, 3 * (d >> 4), G, nsm)) return MILORA_ERANGE;
   // level 1: h = x + L_o(a)
-  reset_stage(l);
-  if (attn_out) { l.X = attn_out; l.ldx = d; }
-  else { l.X = ws.v_pk; l.x_packed = 1; l.sync_before = 1; }
-  l.K = d; l.n_seg = 1;
-  l.W[0] = (const bf16_t*)wts->W[3]; l.N[0] = d; l.site[0] = 3;
-  l.resid_bf16 = x; l.ld_resid = d;
-  l.out_f32 = ws.h_f32; l.ld_f32 = d;
-  l.out_pk = ws.h_pk;
-  if (!push_level(p, l, d >> 4, G, nsm)) return MILORA_ERANGE;
+  {
+    Stage& l = lv[1];
+    reset_stage(l);
+    if (attn_out) { l.X = attn_out; l.ldx = d; }
+    else { l.X = ws.v_pk; l.x_packed = 1; l.sync_before = 1; }
+    l.K = d; l.n_seg = 1;
+    l.W[0] = (const bf16_t*)wts->W[3]; l.N[0] = d; l.site[0] = 3;
+    l.resid_bf16 = x; l.ld_resid = d;
+    l.out_f32 = ws.h_f32; l.ld_f32 = d;
+    l.out_pk = ws.h_pk;
+    l.tpos0 = 3;
+    units[1] = d >> 4;
+  }
   // level 2: m = silu(L_gate(n(h))) * L_up(n(h))
-  reset_stage(l);
-  l.X = ws.h_pk; l.x_packed = 1; l.K = d; l.n_seg = 2; l.pair = 1; l.norm = norm; l.sync_before = 1;
-  for (int s = 0; s < 2; ++s) { l.W[s] = (const bf16_t*)wts->W[4 + s]; l.N[s] = F; l.site[s] = 4 + s; }
-  l.out_pk = ws.m_pk;
-  if (!push_level(p, l, F >> 4, G, nsm)) return MILORA_ERANGE;
+  {
+    Stage& l = lv[2];
+    reset_stage(l);
+    l.X = ws.h_pk; l.x_packed = 1; l.K = d; l.n_seg = 2; l.pair = 1; l.norm = norm; l.sync_before = 1;
+    for (int s = 0; s < 2; ++s) { l.W[s] = (const bf16_t*)wts->W[4 + s]; l.N[s] = F; l.site[s] = 4 + s; }
+    l.out_pk = ws.m_pk;
+    units[2] = F >> 4;
+  }
   // level 3: y = h + L_down(m)
-  reset_stage(l);
-  l.X = ws.m_pk; l.x_packed = 1; l.K = F; l.n_seg = 1; l.sync_before = 1;
-  l.W[0] = (const bf16_t*)wts->W[6]; l.N[0] = d; l.site[0] = 6;
-  l.resid_f32 = ws.h_f32; l.ld_resid = d;
-  l.out[0] = y; l.ld_out[0] = d;
-  if (!push_level(p, l, d >> 4, G, nsm)) return MILORA_ERANGE;
+  {
+    Stage& l = lv[3];
+    reset_stage(l);
+    l.X = ws.m_pk; l.x_packed = 1; l.K = F; l.n_seg = 1; l.sync_before = 1;
+    l.W[0] = (const bf16_t*)wts->W[6]; l.N[0] = d; l.site[0] = 6;
+    l.resid_f32 = ws.h_f32; l.ld_resid = d;
+    l.out[0] = y; l.ld_out[0] = d;
+    l.tpos0 = 3;
+    units[3] = d >> 4;
+  }
+  if (wide) {
+    for (int L = 0; L < 4; ++L) {
+      p.st[L] = lv[L];
+      p.st[L].lora_shrink = 1;
+    }
+    p.n_stages = 4;
+    p.wsegs = wide_segments(MT, d, F);
+    if (MT == 4) hipLaunchKernelGGL(decode_wide_kernel<4>, dim3(G), dim3(kThreads), kLdsBytes, st, p);
+    else hipLaunchKernelGGL(decode_wide_kernel<8>, dim3(G), dim3(kThreads), kLdsBytes, st, p);
+    const int rcw = check_launch();
+    if (rcw) return rcw;
+    if (marks && marks->n > 0) (void)hipEventRecord(marks->ev[0], st);
+    return MILORA_OK;
+  }
+  for (int L = 0; L < 4; ++L)
+    if (!push_level(p, lv[L], units[L], G, nsm)) return MILORA_ERANGE;
   int rc = launch_stream(p, MT, G, st);
   if (rc) return rc;
   if (marks && marks->n > 0) (void)hipEventRecord(marks->ev[0], st);

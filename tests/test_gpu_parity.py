@@ -420,6 +420,51 @@ def test_layer_decode_packed_long_ragged_reduction(B):
     _layer_case(wl, True, mb.W_PACKED)
 
 
+@pytest.mark.parametrize("B", [65, 100, 128])
+@pytest.mark.parametrize("rmsnorm,with_attn", [(False, False), (True, False), (True, True)])
+def test_layer_decode_packed_wide_batches(B, rmsnorm, with_attn):
+    """More than 64 rows take the kernel that cuts each level's reduction over the workgroups: reductions of 65 and
+    73 blocks of 32 (pieces end inside groups and inside input chunks), a batch that does not fill its last row
+    tile, groups that do not fill their last tile slots (390 = 32 * 12 + 6 tiles for q,k,v)."""
+    wl = small(dtype="bf16", d=2080, F=2336, T=8, B=B, ranks=(8, 16, 64), tenants="uniform", seed=300 + B)
+    assert _layer_case(wl, rmsnorm, mb.W_PACKED, with_attn=with_attn) <= TOL[torch.bfloat16]
+
+
+def test_layer_decode_packed_wide_small_level_leaves_workgroups_idle():
+    """d = 64: the o and down levels have 4 tiles, one group of 2 k blocks - fewer positions than workgroups."""
+    wl = small(dtype="bf16", d=64, F=4128, T=3, B=96, ranks=(8,), tenants="uniform", seed=92)
+    assert _layer_case(wl, True, mb.W_PACKED) <= TOL[torch.bfloat16]
+
+
+def test_layer_decode_packed_wide_reuses_buffers_across_steps():
+    """One zero-filled workspace serves many launches of the wide kernel (its segment flags and shrink slots carry
+    the launch's epoch), every step checked; a 32-row call on a workspace of its own runs in between."""
+    wl = small(dtype="bf16", d=1024, F=2752, T=8, B=128, ranks=(16, 32), tenants="uniform", seed=73)
+    wl32 = small(dtype="bf16", d=1024, F=2752, T=8, B=32, ranks=(16, 32), tenants="uniform", seed=73)
+    W, ad, tab = device_layer(wl)
+    Wd = [mb.milora_pack_weight(w) for w in W]
+    tid = synth.tenant_ids(wl)
+    g = torch.Generator().manual_seed(7)
+    route = torch.randint(0, 7, (wl.B,), generator=g).to(torch.uint8)
+    Wn, adn = [np_of(w) for w in W], oracle_adapters(ad)
+    ws = torch.zeros(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, tab.r_max), dtype=torch.uint8, device=DEV)
+    y = torch.empty(wl.B, wl.d, dtype=wl.torch_dtype, device=DEV)
+    qkv = torch.empty(wl.B, 3 * wl.d, dtype=wl.torch_dtype, device=DEV)
+    tid_dev, route_dev = tid.to(DEV), route.to(DEV)
+    for step in range(5):
+        x = synth.decode_input(wl, step, DEV)
+        mb.milora_layer_decode(x, Wd, tab, tid_dev, route_dev, wl.F, w_layout=mb.W_PACKED, rmsnorm=(step % 2 == 0),
+                               y=y, qkv_out=qkv, workspace=ws)
+        if step == 2:
+            mb.milora_layer_decode(synth.decode_input(wl32, step, DEV), Wd, tab, tid_dev[:32].contiguous(),
+                                   route_dev[:32].contiguous(), wl.F, w_layout=mb.W_PACKED)
+        y_ref, qkv_ref = oracle.layer_decode(np_of(x), Wn, adn, tid.numpy(), route.numpy(), wl.F,
+                                             flags=oracle.FLAG_RMSNORM if step % 2 == 0 else 0)
+        assert_rows_close(qkv, qkv_ref, wl.torch_dtype, f"qkv step {step}")
+        assert_rows_close(y, y_ref, wl.torch_dtype, f"y step {step}")
+    assert mb.milora_packed_workspace_status(ws) == 0
+
+
 def test_layer_decode_packed_gate_up_tile_pairs_do_not_fill_the_last_workgroup():
     """F / 16 = 692 gate/up tile pairs over 256 workgroups of 3: the last one with work holds 2 pairs and streams a
     filler pair to keep its rounds whole; the filler's result must be dropped."""
@@ -452,10 +497,11 @@ def test_layer_decode_packed_reuses_buffers_across_steps():
     assert mb.milora_packed_workspace_status(ws) == 0
 
 
-def test_layer_decode_in_a_hip_graph_replays_like_eager():
+@pytest.mark.parametrize("B", [32, 128])
+def test_layer_decode_in_a_hip_graph_replays_like_eager(B):
     """The serving loop captures the decode step once and replays it: every replay, with eager work and
     synchronisations in between, must give bit for bit what the eager call gives on the same input."""
-    wl = small(dtype="bf16", d=1024, F=2752, T=8, B=32, ranks=(16, 32), tenants="uniform", seed=72)
+    wl = small(dtype="bf16", d=1024, F=2752, T=8, B=B, ranks=(16, 32), tenants="uniform", seed=72)
     W, ad, tab = device_layer(wl)
     Wd = [mb.milora_pack_weight(w) for w in W]
     tid = synth.tenant_ids(wl).to(DEV)
@@ -573,6 +619,8 @@ def test_layer_decode_with_route_sets(B, k):
     route[B - 1] = mb.ROUTE_NONE
     assert _layer_case(wl, True, mb.W_PACKED, route=route) <= TOL[torch.bfloat16]
     assert _layer_case(wl, False, mb.W_ROWMAJOR, route=route) <= TOL[torch.bfloat16]
+    # attention output supplied: o follows q,k,v without a grid barrier, and a request can have a LoRA term in both
+    assert _layer_case(wl, True, mb.W_PACKED, with_attn=True, route=route) <= TOL[torch.bfloat16]
 
 
 # ------------------------------------------------------------------------------------------- layer stacks
