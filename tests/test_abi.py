@@ -41,6 +41,14 @@ def test_workspace_sizes_are_monotone_and_reject_bad_sizes():
     a = mb.layer_decode_workspace_bytes(32, 4096, 11008, 32)
     b = mb.layer_decode_workspace_bytes(64, 4096, 11008, 32)
     assert 0 < a < b
+    # above 64 rows the workspace also holds the wide-batch kernel's tables: two halves of (256 workgroups + column
+    # groups of the widest level) segments, each 12 tiles x 8 row tiles of 1 KiB partial sums, a flag and 128 sums
+    # of squares; 11008 / 16 gate/up pairs in groups of 6 = 115 groups
+    c = mb.layer_decode_workspace_bytes(65, 4096, 11008, 32)
+    segs = 2 * (256 + 115)
+    assert c >= segs * (96 * 1024 + 128 * 4 + 4)
+    assert c <= segs * (96 * 1024 + 128 * 4 + 4) + (1 << 23)  # the activations, shrink slots and flags besides
+    assert mb.layer_decode_workspace_bytes(128, 4096, 11008, 32) >= c
     assert mb.layer_decode_workspace_bytes(129, 4096, 11008, 32) == 0  # beyond the decode batch limit
     assert mb.routed_linear_workspace_bytes(32768, 4096, 4096, 32) >= 32768 * 32 * 4
 
