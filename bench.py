@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, vendor figure
 # by what the counter reads for a plain 1 GiB device copy (profiles/decode_layer_llama7b_b32_hbm_counters.txt).
 # Valid only for the kernel source the counters were taken on: keyed by workload and source digest.
 MEASURED_TRAFFIC = {
-    ("llama7b_layer_b32", "909c1befbba20bc3"): {"fetch_bytes": 505272726, "write_bytes": 3694336},
+    ("llama7b_layer_b32", "5d273d6ffba01fc1"): {"fetch_bytes": 505379256, "write_bytes": 3694336},
 }
 
 

@@ -1080,17 +1080,21 @@ constexpr int kWideGridMax = 256;   // workgroups the segment tables are sized f
 __device__ __forceinline__ void st_through(u32x2* p, u32x2 v) {
   asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
 }
-// Four 16-byte loads that bypass the caches (the partial tiles are written by other workgroups in this launch, into
+// Eight 16-byte loads that bypass the caches (the partial tiles are written by other workgroups in this launch, into
 // memory that earlier levels and launches have used), complete when the function returns.
-__device__ __forceinline__ void ld_through4(const f32x4* p0, const f32x4* p1, const f32x4* p2, const f32x4* p3, f32x4 (&v)[4]) {
+__device__ __forceinline__ void ld_through8(const f32x4* const (&q)[8], f32x4 (&v)[8]) {
   asm volatile(
-      "global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
-      "global_load_dwordx4 %1, %5, off sc0 sc1\n\t"
-      "global_load_dwordx4 %2, %6, off sc0 sc1\n\t"
-      "global_load_dwordx4 %3, %7, off sc0 sc1\n\t"
+      "global_load_dwordx4 %0, %8, off sc0 sc1\n\t"
+      "global_load_dwordx4 %1, %9, off sc0 sc1\n\t"
+      "global_load_dwordx4 %2, %10, off sc0 sc1\n\t"
+      "global_load_dwordx4 %3, %11, off sc0 sc1\n\t"
+      "global_load_dwordx4 %4, %12, off sc0 sc1\n\t"
+      "global_load_dwordx4 %5, %13, off sc0 sc1\n\t"
+      "global_load_dwordx4 %6, %14, off sc0 sc1\n\t"
+      "global_load_dwordx4 %7, %15, off sc0 sc1\n\t"
       "s_waitcnt vmcnt(0)"
-      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-      : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+      : "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]), "v"(q[4]), "v"(q[5]), "v"(q[6]), "v"(q[7])
       : "memory");
 }
 
@@ -1452,6 +1456,9 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     }
     // ===================================== all waves: sum, LoRA term, glue, store =====================================
     {
+      // A wave's units share their 16 rows and lie in one group (two at most): a flag that has been seen stays, so
+      // the segment flags of a group and the shrink words of the rows at a site are polled once per wave.
+      int g_seen = -1, sp_seen = -1;
       int uc = 0;
       for (int ti = t0; ti < t1; ++ti)
         for (int mt = 0; mt < MT; ++mt, ++uc) {
@@ -1476,18 +1483,24 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
 #pragma unroll
             for (int z = 0; z < 4; ++z) d[z] = 0.f;
             const bool has = p.lora && m < p.M && ((c.r_mask[m < p.M ? m : 0] >> sg.site[sp]) & 1);
-            const int* f = p.tready + shrink_slot(sg, m < p.M ? m : 0, sp);
-            spin_until([&]() { return __all(!has || ld_agent(f) == lvl_tag); });
+            if (sg.pair ? sp_seen != 3 : sp != sp_seen) {
+              const int* f = p.tready + shrink_slot(sg, m < p.M ? m : 0, sp);
+              spin_until([&]() { return __all(!has || ld_agent(f) == lvl_tag); });
+            }
             if (has) lora_quad(m, sp, ncol, d);
           };
           float da[4], db[4];
           lora_term(s, da);
           if (sg.pair) lora_term(1, db);
+          sp_seen = sg.pair ? 3 : s;  // (a pair polls both of its sites in the first unit)
           // the group's segments are there
-          for (int b = 0; b < n; b += 64) {
-            const int i = b + lane;
-            const int* f = p.segflag + sid0 + (i < n ? i : 0);
-            spin_until([&]() { return __all(i >= n || ld_agent(f) == tag); });
+          if (g != g_seen) {
+            for (int b = 0; b < n; b += 64) {
+              const int i = b + lane;
+              const int* f = p.segflag + sid0 + (i < n ? i : 0);
+              spin_until([&]() { return __all(i >= n || ld_agent(f) == tag); });
+            }
+            g_seen = g;
           }
           f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
           float ssq = 0.f;
@@ -1499,21 +1512,42 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           }
           const size_t sstride = (size_t)NT * MT * 64;
           const f32x4* const P0 = reinterpret_cast<const f32x4*>(p.wpart) + ((size_t)sid0 * NT + a0) * (MT * 64) + mt * 64 + lane;
-          for (int i = 0; i < n; i += 4) {
-            f32x4 v[4];
-            const int i1 = i + 1 < n ? i + 1 : n - 1, i2 = i + 2 < n ? i + 2 : n - 1, i3 = i + 3 < n ? i + 3 : n - 1;
-            ld_through4(P0 + i * sstride, P0 + i1 * sstride, P0 + i2 * sstride, P0 + i3 * sstride, v);
-            sa += v[0];
-            if (i + 1 < n) sa += v[1];
-            if (i + 2 < n) sa += v[2];
-            if (i + 3 < n) sa += v[3];
-            if (sg.pair) {
-              const f32x4* const P1 = P0 + MT * 64;
-              ld_through4(P1 + i * sstride, P1 + i1 * sstride, P1 + i2 * sstride, P1 + i3 * sstride, v);
-              sb += v[0];
-              if (i + 1 < n) sb += v[1];
-              if (i + 2 < n) sb += v[2];
-              if (i + 3 < n) sb += v[3];
+          // bias and residual travel with the partial tiles
+          u32x2 g_bias = {0u, 0u}, g_rb = {0u, 0u};
+          f32x4 g_rf = {0.f, 0.f, 0.f, 0.f};
+          if (m < p.M) {
+            if (sg.bias[s]) g_bias = *reinterpret_cast<const u32x2*>(sg.bias[s] + ncol);
+            if (sg.resid_bf16) g_rb = *reinterpret_cast<const u32x2*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + ncol);
+            if (sg.resid_f32) g_rf = *reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + ncol);
+          }
+          if (sg.pair) {  // gate and up tiles of four segments per round trip
+            for (int i = 0; i < n; i += 4) {
+              const f32x4* q8[8];
+              f32x4 v[8];
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const int iu = i + u < n ? i + u : n - 1;
+                q8[u] = P0 + iu * sstride;
+                q8[4 + u] = P0 + iu * sstride + MT * 64;
+              }
+              ld_through8(q8, v);
+#pragma unroll
+              for (int u = 0; u < 4; ++u)
+                if (i + u < n) {
+                  sa += v[u];
+                  sb += v[4 + u];
+                }
+            }
+          } else {  // eight segments per round trip
+            for (int i = 0; i < n; i += 8) {
+              const f32x4* q8[8];
+              f32x4 v[8];
+#pragma unroll
+              for (int u = 0; u < 8; ++u) q8[u] = P0 + (i + u < n ? i + u : n - 1) * sstride;
+              ld_through8(q8, v);
+#pragma unroll
+              for (int u = 0; u < 8; ++u)
+                if (i + u < n) sa += v[u];
             }
           }
           if (sg.norm) {
@@ -1529,23 +1563,20 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
               val[z] = sg.pair ? silu(v0) * ((sb[z] + db[z]) * inv) : v0;
             }
             if (sg.bias[s]) {
-              const u32x2 bb = *reinterpret_cast<const u32x2*>(sg.bias[s] + ncol);
-              val[0] += __uint_as_float(bb[0] << 16);
-              val[1] += __uint_as_float(bb[0] & 0xffff0000u);
-              val[2] += __uint_as_float(bb[1] << 16);
-              val[3] += __uint_as_float(bb[1] & 0xffff0000u);
+              val[0] += __uint_as_float(g_bias[0] << 16);
+              val[1] += __uint_as_float(g_bias[0] & 0xffff0000u);
+              val[2] += __uint_as_float(g_bias[1] << 16);
+              val[3] += __uint_as_float(g_bias[1] & 0xffff0000u);
             }
             if (sg.resid_bf16) {
-              const u32x2 rr = *reinterpret_cast<const u32x2*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + ncol);
-              val[0] += __uint_as_float(rr[0] << 16);
-              val[1] += __uint_as_float(rr[0] & 0xffff0000u);
-              val[2] += __uint_as_float(rr[1] << 16);
-              val[3] += __uint_as_float(rr[1] & 0xffff0000u);
+              val[0] += __uint_as_float(g_rb[0] << 16);
+              val[1] += __uint_as_float(g_rb[0] & 0xffff0000u);
+              val[2] += __uint_as_float(g_rb[1] << 16);
+              val[3] += __uint_as_float(g_rb[1] & 0xffff0000u);
             }
             if (sg.resid_f32) {
-              const f32x4 rr = *reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + ncol);
 #pragma unroll
-              for (int z = 0; z < 4; ++z) val[z] += rr[z];
+              for (int z = 0; z < 4; ++z) val[z] += g_rf[z];
             }
             if (sg.out_f32) st_through(reinterpret_cast<f32x4*>(sg.out_f32 + (size_t)m * sg.ld_f32 + ncol), f32x4{val[0], val[1], val[2], val[3]});
             const u32x2 o = {pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3])};
