@@ -543,9 +543,10 @@ def test_layer_decode_rowmajor_bf16_matches_too():
     _layer_case(wl, True, mb.W_ROWMAJOR)
 
 
-def test_layer_decode_every_request_on_one_site():
+@pytest.mark.parametrize("B", [20, 128])
+def test_layer_decode_every_request_on_one_site(B):
     # the degenerate route tables: all requests on the same site, and no request routed anywhere
-    wl = small(dtype="bf16", d=256, F=352, T=4, B=20, ranks=(16,), tenants="uniform", seed=52)
+    wl = small(dtype="bf16", d=256, F=352, T=4, B=B, ranks=(16,), tenants="uniform", seed=52)
     for site in (0, 3, 4, 6):
         _layer_case(wl, False, mb.W_PACKED, route=torch.full((wl.B,), site, dtype=torch.uint8))
     _layer_case(wl, False, mb.W_PACKED, route=torch.full((wl.B,), mb.ROUTE_NONE, dtype=torch.uint8))
