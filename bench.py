@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, vendor figure
 # by what the counter reads for a plain 1 GiB device copy (profiles/decode_layer_llama7b_b32_hbm_counters.txt).
 # Valid only for the kernel source the counters were taken on: keyed by workload and source digest.
 MEASURED_TRAFFIC = {
-    ("llama7b_layer_b32", "5d273d6ffba01fc1"): {"fetch_bytes": 505379256, "write_bytes": 3694336},
+    ("llama7b_layer_b32", "773cdd0053fa44a1"): {"fetch_bytes": 505105427, "write_bytes": 3694336},
 }
 
 
@@ -164,7 +164,7 @@ def stack_bench(args, torch, mb, synth, wl, dev):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.L, "d": wl.d, "ffn": wl.F, "batch": wl.B, "tenants": wl.T,
                    "ranks": list(wl.ranks), "routes": "constructed table", "hip_graph": not args.no_graph},
-        "roofline": {"bound": "hbm", "kernel": ("decode_wide_kernel" if wl.B > 64 else "decode_stream_kernel") + " (L launches per step)", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": ("decode_wide_kernel" if wl.B > 32 else "decode_stream_kernel") + " (L launches per step)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "algorithmic_bytes_per_step": nbytes, "us_per_layer": round(ms * 1e3 / wl.L, 2)},
         "cpu_baseline": None}))

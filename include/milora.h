@@ -195,7 +195,7 @@ int milora_routed_linear(const void *X, int64_t M, int d1, int d2, int dtype,
  *   weights   host struct of the seven base weights
  *   attn_out  device [B][d] `dtype` or NULL
  *   qkv_out   device [B][3d] `dtype` or NULL: q | k | v of every request, for the caller's attention
- *   workspace device, milora_layer_decode_workspace_bytes(B, d, F, r_max) bytes (packed weights and B > 64:
+ *   workspace device, milora_layer_decode_workspace_bytes(B, d, F, r_max) bytes (packed weights and B > 32:
  *             this includes the tables of fp32 partial tiles of the wide-batch kernel, tens of MB)
  * Errors: EINVAL, ERANGE (B > MILORA_MAX_DECODE_BATCH, r_max > MILORA_MAX_RANK), EUNSUPPORTED
  * (packed layout with fp32, with d or F not a multiple of 32, or with x, y, attn_out, qkv_out or a

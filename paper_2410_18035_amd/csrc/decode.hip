@@ -1063,7 +1063,7 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const u32x4* __restric
 }
 
 // =====================================================================================================================
-// Wide batches (65..128 rows; the code also serves 33..64, where it is no faster than the stream kernel).  With this many rows the stage input is as large as a workgroup's share of the weights,
+// Wide batches (33..128 rows).  With this many rows the stage input is as large as a workgroup's share of the weights,
 // and a workgroup that owns a few 16-column tiles over the whole reduction reads all of it: the input copies, not the
 // weights, set the time.  Here a level (q,k,v | o | gate,up | down) is cut the other way: a group is kSW * TPW tiles
 // wide (each stream wave holds TPW tiles of it, over all rows), the (group, k block) space of a level is laid out in a
@@ -1731,7 +1731,7 @@ struct DecodeWs {
   bf16_t* v_pk;    // a = v as operand blocks   (K = d)
   bf16_t* h_pk;    // h as operand blocks       (K = d)
   bf16_t* m_pk;    // m = silu(g) * u as operand blocks (K = F)
-  int* segflag;    // wide kernel, layer decode of more than 64 rows only: see Params
+  int* segflag;    // wide kernel, layer decode of more than 32 rows only: see Params
   float* wss;
   float* wpart;
   size_t bytes;
@@ -1774,7 +1774,7 @@ void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const
 
 }  // namespace
 
-size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max) { return carve_decode_ws(nullptr, M, d, F, r_max, M > 64).bytes; }
+size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max) { return carve_decode_ws(nullptr, M, d, F, r_max, M > 32).bytes; }
 
 // The word the stream kernels set when one of their bounded waits ran out (it lies at the same place in every
 // workspace of the packed paths).  Waits for the stream's work, then copies the word to the host.
@@ -1791,11 +1791,11 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
                         const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
                         bf16_t* y, bf16_t* qkv_out, void* workspace, hipStream_t st, LaunchMarks* marks) {
   const int MT = mt_for(B);
-  const bool wide = MT >= 8;  // more than 64 rows: the kernel that cuts the reduction over the workgroups
+  const bool wide = MT >= 4;  // more than 32 rows: the kernel that cuts the reduction over the workgroups
   const int G = wide ? (MT == 4 ? wide_grid<4>() : wide_grid<8>()) : grid_for(MT);
   if (G <= 0) return hip_fail(hipGetLastError());
   const int nsm = ns_max_for(MT);
-  DecodeWs ws = carve_decode_ws(workspace, B, d, F, ad.r_max, B > 64);
+  DecodeWs ws = carve_decode_ws(workspace, B, d, F, ad.r_max, B > 32);
   const int norm = (flags & MILORA_LAYER_RMSNORM) ? 1 : 0;
   Params p;
   fill_common(p, ws, B, B, F > d ? F : d, ad, tenant_id, route, nullptr);

@@ -38,16 +38,18 @@ def test_status_strings_and_version():
 def test_workspace_sizes_are_monotone_and_reject_bad_sizes():
     assert mb.route_workspace_bytes(0, 4096, 100) == 0
     assert mb.route_workspace_bytes(32, 4096, 8192) >= 32 * 4096 * 4
-    a = mb.layer_decode_workspace_bytes(32, 4096, 11008, 32)
-    b = mb.layer_decode_workspace_bytes(64, 4096, 11008, 32)
+    a = mb.layer_decode_workspace_bytes(16, 4096, 11008, 32)
+    b = mb.layer_decode_workspace_bytes(32, 4096, 11008, 32)
     assert 0 < a < b
-    # above 64 rows the workspace also holds the wide-batch kernel's tables: two halves of (256 workgroups + column
-    # groups of the widest level) segments, each 12 tiles x 8 row tiles of 1 KiB partial sums, a flag and 128 sums
-    # of squares; 11008 / 16 gate/up pairs in groups of 6 = 115 groups
+    # above 32 rows the workspace also holds the wide-batch kernel's tables: two halves of (256 workgroups + column
+    # groups of the widest level) segments, each 96 tiles of 1 KiB partial sums (24 tiles x 4 row tiles up to 64
+    # rows, 12 x 8 above), a flag and the rows' sums of squares; 11008 / 16 gate/up pairs in groups of 12 or 6
+    c = mb.layer_decode_workspace_bytes(33, 4096, 11008, 32)
+    segs = 2 * (256 + 58)
+    assert segs * (96 * 1024 + 64 * 4 + 4) <= c <= segs * (96 * 1024 + 64 * 4 + 4) + (1 << 23)
     c = mb.layer_decode_workspace_bytes(65, 4096, 11008, 32)
     segs = 2 * (256 + 115)
-    assert c >= segs * (96 * 1024 + 128 * 4 + 4)
-    assert c <= segs * (96 * 1024 + 128 * 4 + 4) + (1 << 23)  # the activations, shrink slots and flags besides
+    assert segs * (96 * 1024 + 128 * 4 + 4) <= c <= segs * (96 * 1024 + 128 * 4 + 4) + (1 << 23)
     assert mb.layer_decode_workspace_bytes(128, 4096, 11008, 32) >= c
     assert mb.layer_decode_workspace_bytes(129, 4096, 11008, 32) == 0  # beyond the decode batch limit
     assert mb.routed_linear_workspace_bytes(32768, 4096, 4096, 32) >= 32768 * 32 * 4

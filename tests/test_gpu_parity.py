@@ -420,12 +420,12 @@ def test_layer_decode_packed_long_ragged_reduction(B):
     _layer_case(wl, True, mb.W_PACKED)
 
 
-@pytest.mark.parametrize("B", [65, 100, 128])
+@pytest.mark.parametrize("B", [33, 64, 65, 100, 128])
 @pytest.mark.parametrize("rmsnorm,with_attn", [(False, False), (True, False), (True, True)])
 def test_layer_decode_packed_wide_batches(B, rmsnorm, with_attn):
-    """More than 64 rows take the kernel that cuts each level's reduction over the workgroups: reductions of 65 and
+    """More than 32 rows take the kernel that cuts each level's reduction over the workgroups: reductions of 65 and
     73 blocks of 32 (pieces end inside groups and inside input chunks), a batch that does not fill its last row
-    tile, groups that do not fill their last tile slots (390 = 32 * 12 + 6 tiles for q,k,v)."""
+    tile, groups that do not fill their last tile slots (390 = 32 * 12 + 6 = 16 * 24 + 6 tiles for q,k,v)."""
     wl = small(dtype="bf16", d=2080, F=2336, T=8, B=B, ranks=(8, 16, 64), tenants="uniform", seed=300 + B)
     assert _layer_case(wl, rmsnorm, mb.W_PACKED, with_attn=with_attn) <= TOL[torch.bfloat16]
 
