@@ -552,7 +552,8 @@ def test_layer_decode_every_request_on_one_site(B):
     _layer_case(wl, False, mb.W_PACKED, route=torch.full((wl.B,), mb.ROUTE_NONE, dtype=torch.uint8))
 
 
-def test_headline_shape_one_step_full_parity():
+@pytest.mark.parametrize("rmsnorm", [False, True])
+def test_headline_shape_one_step_full_parity(rmsnorm):
     """LLaMA-2-7B-shaped layer, batch 32, 32 tenants, rank 32, packed weights: the benchmark configuration."""
     wl = synth.CONFIGS["llama7b_layer_b32"]
     H, ss, sl = synth.prompts(wl, 0, DEV)
@@ -562,8 +563,19 @@ def test_headline_shape_one_step_full_parity():
     ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[wl.pool], mb.ACT[wl.act])
     excluded = assert_routes_match(route, ref, torch.bfloat16, "7B routes")
     assert excluded <= 0.1
-    worst = _layer_case(wl, False, mb.W_PACKED, steps=1, route=torch.from_numpy(ref.route.copy()))
+    worst = _layer_case(wl, rmsnorm, mb.W_PACKED, steps=1, route=torch.from_numpy(ref.route.copy()))
     print(f"7B layer: excluded routes {excluded:.3f}, worst row rel err {worst:.3e}")
+
+
+@pytest.mark.parametrize("B", [64, 128])
+def test_llama7b_layer_wide_batches_all_rows(B):
+    """The 7B-shaped layer at 64 and 128 requests (the kernel for more than 32 rows at its real shapes: 256 workgroups,
+    pieces of 32 to 344 k blocks, 2 to 12 segments per column group), every row against the oracle."""
+    wl = dataclasses.replace(synth.CONFIGS["llama7b_layer_b32"], B=B, T=B)
+    g = torch.Generator().manual_seed(9)
+    route = torch.randint(0, 7, (B,), generator=g).to(torch.uint8)
+    route[5] = mb.ROUTE_NONE
+    assert _layer_case(wl, True, mb.W_PACKED, route=route) <= TOL[torch.bfloat16]
 
 
 # ------------------------------------------------------------------------------------------- several experts per request
