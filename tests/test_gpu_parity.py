@@ -578,6 +578,14 @@ def test_llama7b_layer_wide_batches_all_rows(B):
     assert _layer_case(wl, True, mb.W_PACKED, route=route) <= TOL[torch.bfloat16]
 
 
+def test_llama13b_layer_128_requests_route_sets_all_rows():
+    """One 13B-shaped layer, 128 requests of 128 tenants with ranks 8/16/64, two experts per request, attention
+    output supplied (o follows q,k,v without a barrier): every row against the oracle."""
+    wl = synth.CONFIGS["llama13b_stack_b128"]
+    route = _route_sets(wl.B, 2, 13)
+    assert _layer_case(wl, True, mb.W_PACKED, with_attn=True, route=route) <= TOL[torch.bfloat16]
+
+
 # ------------------------------------------------------------------------------------------- several experts per request
 def _route_sets(B, k, seed):
     """Route bytes MILORA_ROUTE_SET | mask with k sites each, drawn per request (the table is an input of decode)."""
