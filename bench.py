@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, vendor figure
 # by what the counter reads for a plain 1 GiB device copy (profiles/decode_layer_llama7b_b32_hbm_counters.txt).
 # Valid only for the kernel source the counters were taken on: keyed by workload and source digest.
 MEASURED_TRAFFIC = {
-    ("llama7b_layer_b32", "773cdd0053fa44a1"): {"fetch_bytes": 505105427, "write_bytes": 3694336},
+    ("llama7b_layer_b32", "397a6776a1f1db84"): {"fetch_bytes": 504844354, "write_bytes": 3694336},
 }
 
 

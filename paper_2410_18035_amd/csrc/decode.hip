@@ -908,6 +908,9 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       }
   };
 
+  // The two tail waves issue ahead of the stream waves: their copies, polls and stores lie on the path of every stage
+  // end, while a stream wave that waits a few cycles for an issue slot loses nothing its ring has not covered.
+  __builtin_amdgcn_s_setprio(3);
   int nseq = 0;  // input chunks of the earlier stages
   if (w == kLoader) {
     // ===================================== input loader =====================================
@@ -1187,6 +1190,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     }
   };
 
+  if (w >= kSW) __builtin_amdgcn_s_setprio(3);  // the loader and LoRA waves issue ahead of the stream waves
   int xs = 0;      // input chunks of the segments so far (the same count in every wave)
   int segord = 0;  // segments so far
   int seen = 0;    // stream waves: chunks known to have landed
