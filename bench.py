@@ -20,24 +20,32 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, vendor figure
 
-# HBM bytes per launch of the decode kernel from the FETCH_SIZE and WRITE_SIZE hardware counters, each scaled
-# by what the counter reads for a plain 1 GiB device copy (profiles/decode_layer_llama7b_b32_hbm_counters.txt).
-# Valid only for the kernel source the counters were taken on: keyed by workload and source digest.
-MEASURED_TRAFFIC = {
-    ("llama7b_layer_b32", "397a6776a1f1db84"): {"fetch_bytes": 504844354, "write_bytes": 3694336},
-}
-
-
-def measured_traffic(workload):
+def source_digest():
+    """Digest of the decode kernels' source: hardware-counter figures are valid for the source they were taken on."""
     import hashlib
 
     src = os.path.join(ROOT, "paper_2410_18035_amd", "csrc", "decode.hip")
     try:
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        return hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
     except OSError:
         return None
-    m = MEASURED_TRAFFIC.get((workload, digest))
-    return None if m is None else m["fetch_bytes"] + m["write_bytes"]
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the workload's decode kernel from the FETCH_SIZE and WRITE_SIZE hardware counters,
+    each scaled by what the counter reads for a plain 1 GiB device copy.  The figures live in the counter summaries
+    under profiles/ (a line `bench-traffic: workload=... source=... fetch_bytes=... write_bytes=...`); None when
+    there is none for this workload or the kernel source has changed since the counters were taken."""
+    import glob
+    import re
+
+    digest = source_digest()
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*hbm_counters*.txt"))):
+        for line in open(path):
+            m = re.match(r"\s*bench-traffic:\s*workload=(\S+)\s+source=(\S+)\s+fetch_bytes=(\d+)\s+write_bytes=(\d+)", line)
+            if m and m.group(1) == workload and m.group(2) == digest:
+                return int(m.group(3)) + int(m.group(4))
+    return None
 
 
 def algorithmic_bytes(wl, routes, tenant_ids, ranks):
@@ -108,22 +116,65 @@ def prefill_leg(torch, mb, synth, dev, reps=5):
             "route_pool_gbs": round(valid_bytes / (route_ms * 1e-3) / 1e9, 1)}
 
 
+def bf16_bits(torch, synth, y64):
+    """fp64 values -> the bf16 bit patterns a layer's output is stored as (the next layer's input)."""
+    import numpy as np
+
+    return synth.as_numpy(torch.from_numpy(np.ascontiguousarray(y64)).to(torch.bfloat16))
+
+
+def row_rel_err(np, y, ref):
+    denom = np.abs(ref).max(axis=1)
+    return float((np.abs(y - ref).max(axis=1) / np.where(denom == 0, 1.0, denom)).max())
+
+
 def stack_bench(args, torch, mb, synth, wl, dev):
     """Multi-layer decode stacks (not the headline workload): every layer's packed weights and adapters resident
-    in HBM, routes as a given table, one step = one token for all B requests through all L layers."""
-    tid = synth.tenant_ids(wl).to(dev)
-    table = synth.constructed_routes(wl).to(dev)
+    in HBM, routes as a given table, one step = one token for all B requests through all L layers.  The oracle
+    follows a seeded sample of the requests through the same stack on the host cores while the layers are being
+    built (requests are independent rows through the whole chain): its time, scaled by B / sample, is the CPU
+    baseline of one step."""
+    import random
+
+    import numpy as np
+
+    tid_host = synth.tenant_ids(wl)
+    tid = tid_host.to(dev)
+    table_host = synth.constructed_routes(wl)
+    table = table_host.to(dev)
+    x0 = synth.decode_input(wl, 0, dev)
+    cpu_on = not args.no_cpu_baseline
+    sample = sorted(random.Random(0).sample(range(wl.B), min(wl.B, 32)))
+    if cpu_on:
+        import oracle
+
+        xr = synth.as_numpy(x0[sample])
+        tid_s = np.arange(len(sample), dtype=np.int32)
+        t_cpu, y_first_ref, y_last_ref = 0.0, None, None
     layers, nbytes = [], 0
     for layer in range(wl.L):
         W = synth.base_weights(wl, layer, dev)
         Wp = [mb.milora_pack_weight(w) for w in W]
-        del W
         ad = synth.adapters(wl, layer, dev)
         tab = mb.AdapterTable.from_tensors(ad.A, ad.B, ad.rank)
         layers.append((Wp, ad, tab))
-        nbytes += algorithmic_bytes(wl, table[layer].cpu().numpy(), tid.cpu().numpy(), ad.rank)["layer_step"]
+        nbytes += algorithmic_bytes(wl, table_host[layer].numpy(), tid_host.numpy(), ad.rank)["layer_step"]
+        if cpu_on:
+            Wn = [synth.as_numpy(w) for w in W]
+            sub = [int(tid_host[b]) for b in sample]
+            adn = oracle.Adapters([[synth.as_numpy(a) for a in ad.A[t]] for t in sub],
+                                  [[synth.as_numpy(b) for b in ad.B[t]] for t in sub], [ad.rank[t] for t in sub])
+            t0 = time.perf_counter()
+            y_ref, _ = oracle.layer_decode(xr, Wn, adn, tid_s, table_host[layer][sample].numpy(), wl.F,
+                                           flags=oracle.FLAG_RMSNORM if wl.rmsnorm else 0)
+            t_cpu += time.perf_counter() - t0
+            xr = bf16_bits(torch, synth, y_ref)
+            if layer == 0:
+                y_first_ref = y_ref
+            y_last_ref = y_ref
+            del Wn, adn
+        del W
     ws = torch.zeros(mb.layer_decode_workspace_bytes(wl.B, wl.d, wl.F, max(wl.ranks)), dtype=torch.uint8, device=dev)
-    x0 = synth.decode_input(wl, 0, dev)
     bufs = [torch.empty_like(x0), torch.empty_like(x0)]
     qkv = torch.empty(wl.B, 3 * wl.d, dtype=x0.dtype, device=dev)
 
@@ -137,6 +188,14 @@ def stack_bench(args, torch, mb, synth, wl, dev):
 
     step()
     torch.cuda.synchronize()
+    parity = None
+    if cpu_on:
+        y_last = bufs[(wl.L - 1) & 1][sample].double().cpu().numpy()
+        y_first, _ = mb.milora_layer_decode(x0, layers[0][0], layers[0][2], tid, table[0], wl.F, w_layout=mb.W_PACKED,
+                                            rmsnorm=wl.rmsnorm, workspace=ws)
+        parity = {"sampled_requests": len(sample),
+                  "first_layer_worst_row_rel_err": row_rel_err(np, y_first[sample].double().cpu().numpy(), y_first_ref),
+                  "free_running_chains_after_all_layers": row_rel_err(np, y_last, y_last_ref)}
     run = step
     if not args.no_graph:
         side = torch.cuda.Stream()
@@ -157,17 +216,34 @@ def stack_bench(args, torch, mb, synth, wl, dev):
         run()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
+    status = mb.milora_packed_workspace_status(ws)
+    assert status == 0, "a hand-over inside a decode launch timed out: the figures would be of wrong results"
+    # the launches one by one, HIP events on the launch stream around each (the step above is one graph)
+    _, _, slot_ms = mb.milora_layer_decode(x0, layers[0][0], layers[0][2], tid, table[0], wl.F, w_layout=mb.W_PACKED,
+                                           rmsnorm=wl.rmsnorm, y=bufs[0], qkv_out=qkv, workspace=ws,
+                                           profile_reps=args.profile_reps)
     achieved = nbytes / (ms * 1e-3) / 1e9
+    cpu = None
+    if cpu_on:
+        cpu_step_s = t_cpu * wl.B / len(sample)
+        cpu = {"value": round(wl.B / cpu_step_s, 2), "unit": "tokens/s", "cores": min(oracle.n_threads(), len(sample)),
+               "kind": "oracle",
+               "sample": f"one decode step of {len(sample)} of the {wl.B} requests through all {wl.L} layers "
+                         f"({t_cpu:.1f} s), scaled by {wl.B}/{len(sample)} (requests are independent rows)"}
+    kernel = "decode_wide_kernel" if wl.B > 32 else "decode_stream_kernel"
+    traffic = measured_traffic(wl.name)
     print(json.dumps({
         "metric": "routed-LoRA decode tokens/s through the layer stack + % HBM roofline", "value": round(wl.B / (ms * 1e-3), 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.L, "d": wl.d, "ffn": wl.F, "batch": wl.B, "tenants": wl.T,
                    "ranks": list(wl.ranks), "routes": "constructed table", "hip_graph": not args.no_graph},
-        "roofline": {"bound": "hbm", "kernel": ("decode_wide_kernel" if wl.B > 32 else "decode_stream_kernel") + " (L launches per step)", "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "algorithmic_bytes_per_step": nbytes, "us_per_layer": round(ms * 1e3 / wl.L, 2)},
-        "cpu_baseline": None}))
+        "roofline": {"bound": "hbm", "kernel": kernel + " (L launches per step)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None if traffic is None else traffic * wl.L,
+                     "algorithmic_bytes_per_step": nbytes, "us_per_layer": round(ms * 1e3 / wl.L, 2),
+                     "first_layer_launch_us": round(slot_ms[0] * 1e3, 2)},
+        "cpu_baseline": cpu, "parity": parity}))
 
 
 def main():
@@ -176,6 +252,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_layer_b32")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="single-layer workloads: run the layer with this many requests (and as many tenants) "
+                         "instead of the workload's own batch, e.g. 64 or 128 on llama7b_layer_b32")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the many-row (prefill configuration) leg")
@@ -202,6 +281,10 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.CONFIGS[args.workload]
     assert wl.dtype == "bf16" and wl.decode_steps > 0, "the benchmark runs the bf16 decode configurations"
+    if args.batch and wl.L == 1:
+        import dataclasses
+
+        wl = dataclasses.replace(wl, name=f"{wl.name.rsplit('_b', 1)[0]}_b{args.batch}", B=args.batch, T=args.batch)
     if wl.L > 1:
         stack_bench(args, torch, mb, synth, wl, dev)
         return
@@ -282,12 +365,15 @@ def main():
     achieved = nbytes["layer_step"] / (dominant_ms * 1e-3) / 1e9
     layer_ms = sum(slot_ms)
     decode_ms_in_step = (ms_per_step - route_ms) / nsteps
-    roofline = {"bound": "hbm", "kernel": "decode_stream_kernel (one decode step of the layer)", "achieved": round(achieved, 1),
+    assert mb.milora_packed_workspace_status(ws_layer) == 0, \
+        "a hand-over inside a decode launch timed out: the figures would be of wrong results"
+    kernel = "decode_wide_kernel" if wl.B > 32 else "decode_stream_kernel"
+    roofline = {"bound": "hbm", "kernel": kernel + " (one decode step of the layer)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name),
                 "algorithmic_bytes_per_launch": nbytes["layer_step"], "avg_launch_ms": round(dominant_ms, 5)}
 
     # ---- the oracle on the host cores, bounded sample ---------------------------------------------
-    cpu = None
+    cpu, parity = None, None
     if not args.no_cpu_baseline:
         import oracle
 
@@ -298,13 +384,20 @@ def main():
         t0 = time.perf_counter()
         ref = oracle.route(Hn, ss_host.numpy(), sl_host.numpy(), tid_host.numpy(), Wrn, mb.POOL[wl.pool], mb.ACT[wl.act])
         t_route = time.perf_counter() - t0
-        done, t_dec = 0, 0.0
+        # decode reuses the cached table: the oracle gets the routes the GPU's router wrote
+        margin = 1e-3 * float(ref.logits.std())
+        keep = ref.gap >= margin
+        done, t_dec, worst = 0, 0.0, 0.0
         while done < nsteps and (done < 1 or t_dec + t_dec / done < 20.0):
             t0 = time.perf_counter()
-            oracle.layer_decode(synth.as_numpy(xs[done]), Wn, adn, tid_host.numpy(), ref.route, wl.F,
-                                flags=oracle.FLAG_RMSNORM if wl.rmsnorm else 0)
+            y_ref, _ = oracle.layer_decode(synth.as_numpy(xs[done]), Wn, adn, tid_host.numpy(), route_host, wl.F,
+                                           flags=oracle.FLAG_RMSNORM if wl.rmsnorm else 0)
             t_dec += time.perf_counter() - t0
+            worst = max(worst, row_rel_err(np, ys[done].double().cpu().numpy(), y_ref))
             done += 1
+        parity = {"routes_differing_outside_margin": int((keep & (route_host != ref.route)).sum()),
+                  "routes_excluded_as_near_ties": int((~keep).sum()), "route_margin": margin,
+                  "decode_steps_checked": done, "worst_row_rel_err": worst}
         cpu_step_s = t_route + t_dec / done * nsteps
         cpu = {"value": round(tokens_per_step / cpu_step_s, 2), "unit": "tokens/s", "cores": oracle.n_threads(),
                "kind": "oracle",
@@ -334,6 +427,7 @@ def main():
                    "tokens_per_step": tokens_per_step, "weights": "bf16 packed", "hip_graph": graph is not None},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "parity": parity,
         "measured_ceilings": ceilings,
         "prefill": prefill,
         "layer_step": {"us_in_timed_region": round(decode_ms_in_step * 1e3, 2),

@@ -210,13 +210,24 @@ int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
 
 /* ------------------------------------------------------------------------------------------------
  * milora_packed_workspace_status - the packed-weight kernels (milora_layer_decode and milora_routed_linear
- * with MILORA_W_PACKED) hand data from one workgroup to another inside a launch and wait for it with bounded
- * polls; a wait that runs out (it never should) sets a word in the workspace to 1 and the launch finishes with
- * wrong results instead of hanging.  This call waits for the work queued on `stream`, then copies that word
- * to *status (host): 0 = every wait ended normally since the workspace was zero-filled.
+ * with MILORA_W_PACKED) run as ONE launch of one workgroup per compute unit whose workgroups hand data to each
+ * other inside the launch (the four dependent levels of a layer step) and wait for it with bounded polls.
+ * That needs all workgroups of the launch resident at the same time: a packed-path launch must not overlap
+ * other GPU work of the process (another stream's kernels, a second packed-path launch on another workspace)
+ * that holds compute units.  When it does, or after a fault elsewhere, a wait runs out after
+ * milora_set_wait_limit() polls (seconds with the default): the wave that waited sets a word in the workspace
+ * to 1 and ends, the waves that depend on it run out the same way, and the launch finishes with wrong or
+ * missing results instead of hanging.  This call waits for the work queued on `stream`, then copies that word
+ * to *status (host): 0 = every wait ended normally since the workspace was zero-filled.  After a 1 the
+ * workspace must be zero-filled again before its next use.
  * Errors: EINVAL, EHIP.
  */
 int milora_packed_workspace_status(const void *workspace, int *status, void *stream);
+/* Polls after which a bounded wait of the packed-weight kernels gives up, for the launches enqueued after this
+ * call by any thread; polls <= 0 restores the default (2^22, a few seconds).  Returns the previous value.  A
+ * service that prefers a fast failure to a long wait lowers it; a value of a few polls makes every wait that
+ * is not satisfied at once run out, which is how the error path is tested. */
+int milora_set_wait_limit(int polls);
 
 /* ------------------------------------------------------------------------------------------------
  * milora_layer_decode_profile - measurement aid, not part of the method: runs milora_layer_decode

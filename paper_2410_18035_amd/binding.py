@@ -33,7 +33,7 @@ EXPORTS = (
     "milora_route_workspace_bytes", "milora_route",
     "milora_routed_linear_workspace_bytes", "milora_routed_linear_kernel", "milora_routed_linear",
     "milora_layer_decode_workspace_bytes", "milora_layer_decode", "milora_layer_decode_profile",
-    "milora_pack_weight", "milora_packed_workspace_status",
+    "milora_pack_weight", "milora_packed_workspace_status", "milora_set_wait_limit",
     "milora_measure_workspace_bytes", "milora_measure_matrix_rate", "milora_measure_read_rate",
 )
 
@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.milora_pack_weight.argtypes = [vp, vp, i32, i32, vp]
         L.milora_packed_workspace_status.restype = i32
         L.milora_packed_workspace_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int), vp]
+        L.milora_set_wait_limit.restype = i32
+        L.milora_set_wait_limit.argtypes = [i32]
         L.milora_measure_workspace_bytes.restype = sz
         L.milora_measure_workspace_bytes.argtypes = []
         L.milora_measure_matrix_rate.restype = i32
@@ -333,6 +335,11 @@ def milora_measure_read_rate(buf: torch.Tensor, reps: int = 5) -> float:
     if rc:
         raise MiloraError(rc, "milora_measure_read_rate")
     return out.value
+
+
+def milora_set_wait_limit(polls: int) -> int:
+    """Polls after which a bounded wait inside a packed-weight launch gives up (<= 0: the default); returns the old value."""
+    return int(lib().milora_set_wait_limit(int(polls)))
 
 
 def milora_packed_workspace_status(workspace: torch.Tensor) -> int:

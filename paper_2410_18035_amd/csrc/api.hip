@@ -17,6 +17,7 @@ int routed_linear_packed(const bf16_t* X, int M, int d1, int d2, const int32_t* 
                          const uint8_t* route, int B, bf16_t* Y, void* workspace, hipStream_t st);
 size_t routed_linear_packed_workspace_bytes(int M, int d1, int d2, int r_max);
 int pack_weight(const void* src, void* dst, int d1, int d2, hipStream_t st);
+int set_wait_limit(int polls);
 // prefill.hip
 int decode_workspace_status(const void* workspace, int* status, hipStream_t st);
 bool prefill_supported(int64_t M, int d1, int d2, const void* X, const void* W, const void* Y);
@@ -277,6 +278,8 @@ extern "C" int milora_packed_workspace_status(const void* workspace, int* status
   if (!workspace || !status) return MILORA_EINVAL;
   return decode_workspace_status(workspace, status, (hipStream_t)stream);
 }
+
+extern "C" int milora_set_wait_limit(int polls) { return set_wait_limit(polls); }
 
 extern "C" size_t milora_layer_decode_workspace_bytes(int B, int d, int F, int r_max) {
   if (B < 1 || d < 1 || F < 1 || r_max < 1 || B > MILORA_MAX_DECODE_BATCH) return 0;

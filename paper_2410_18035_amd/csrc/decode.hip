@@ -20,6 +20,7 @@
 // silu*up) applied, one rounding to bf16.  Stages that depend on each other are separated by a
 // grid barrier of per-workgroup flags (monotone values, nothing to reset between launches).
 // All sums run in a fixed order: results do not depend on timing.
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -47,7 +48,7 @@ constexpr int kMaxRows = MILORA_MAX_DECODE_BATCH;
 constexpr int kMaxGrid = 1024;          // workgroups the barrier flags are sized for
 constexpr int kShrinkChunk = 512;       // reduction rows per LoRA shrink item
 constexpr int kSteady = 8;              // weight loads per stream wave in flight between stage ends
-constexpr int kSpinLimit = 1 << 22;     // polls before a bounded wait gives up
+constexpr int kSpinLimit = 1 << 22;     // polls before a bounded wait gives up (unless the caller set another limit)
 constexpr int kCtrlBytes = 12288;       // control block at the start of LDS
 constexpr int kLdsBytes = 160 * 1024;       // all of a compute unit's LDS: one workgroup per unit
 
@@ -58,6 +59,9 @@ template <> struct Cfg<1> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELT
 template <> struct Cfg<2> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELTA = 8192; };
 template <> struct Cfg<4> { static constexpr int D = 12, NS = 6, CHAIN = 3, DELTA = 8192; };
 template <> struct Cfg<8> { static constexpr int D = 12, NS = 2, CHAIN = 3, DELTA = 2048; };
+
+// Polls after which a bounded wait inside a launch gives up; the launches that follow a change use the new value.
+std::atomic<int> g_wait_limit{kSpinLimit};
 
 struct Stage {
   const bf16_t* X;  // input rows: row-major bf16 [M][ldx], or operand blocks (x_packed, see packed_x_offset)
@@ -100,6 +104,7 @@ struct Params {
   int wsegs;      // wide kernel: segments per table half (even levels use the first half of the three tables, odd the second)
   int* flags;     // [kMaxGrid] grid barrier flags, monotone
   int* status;    // set to 1 when a bounded wait ran out
+  int spin_limit; // polls before a bounded wait gives up
   Stage st[kMaxStages];
 };
 
@@ -217,14 +222,23 @@ __device__ __forceinline__ float sumsq8(u32x4 v) {
 __host__ __device__ __forceinline__ int shrink_chunks(int K) { return (K + kShrinkChunk - 1) / kShrinkChunk; }
 
 
+// A bounded wait ran out (another launch holds compute units this one needs, or a fault elsewhere): record it and
+// end this wave.  What it waited for never came, so nothing it would do next has its inputs; the waves and
+// workgroups that wait for this one run out the same way, and the launch ends with every wave gone.
+__device__ __forceinline__ void give_up(int* status) {
+  st_agent(status, 1);
+  wait_all_mem();
+  __builtin_amdgcn_endpgm();
+}
+
 // Wait until every workgroup has published `target`.  One wave.
-__device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, int lane) {
+__device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, int lane, int limit) {
   int spins = 0;
   for (;;) {
     bool ok = true;
     for (int i = lane; i < G; i += 64) ok = ok && (ld_agent(flags + i) - target >= 0);
     if (__all(ok)) break;
-    if (++spins >= kSpinLimit) return false;
+    if (++spins >= limit) return false;
     __builtin_amdgcn_s_sleep(2);
   }
   // No cache invalidation here: what later stages read (the packed activations, the fp32 residual) is written
@@ -438,7 +452,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   auto spin_until = [&](auto cond) __attribute__((always_inline)) {
     int spins = 0;
     while (!cond()) {
-      if (++spins >= kSpinLimit) break;
+      if (++spins >= p.spin_limit) give_up(p.status);
       __builtin_amdgcn_s_sleep(1);
     }
     compiler_fence();
@@ -452,6 +466,21 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
 
   if (w < kSW) {
     // ===================================== stream waves =====================================
+    // These waves wait for LDS words only and address memory through nothing they wait for: after a wait that ran
+    // out (the loader or the LoRA wave has given up) they record it, skip every later wait and run to the end of
+    // their loop on whatever the buffers hold.
+    bool dead = false;
+    auto spin_until = [&](auto cond) __attribute__((always_inline)) {
+      int spins = 0;
+      while (!dead && !cond()) {
+        if (++spins >= p.spin_limit) {
+          st_agent(p.status, 1);
+          dead = true;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      compiler_fence();
+    };
     u32x4 ring[D];
     f32x4 acc[NSMAX][MT];
     // producer state, uniform over the wave
@@ -921,7 +950,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       const int NCH = chunks_of(NS, KT);
       const int NBUF = nbuf_of(NS);
       if (sg.sync_before && L > 0) {
-        if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
+        if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
       }
       load_input(L, sg, KT, NS, NCH, NBUF, nseq, 0);
       nseq += NCH;
@@ -944,7 +973,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       if (sg.lora_shrink) lvl_tag = epoch * 16 + L + 1;  // a slot can serve several levels of one launch
       if (p.lora && sg.lora_shrink) {
         if (sg.sync_before && L > 0) {
-          if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
+          if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
         }
         // the rows with a LoRA term at one of this level's sites, in row order (the same list in every workgroup)
         if (lane == 0) c.s_cnt = 0;
@@ -970,7 +999,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       if (kLoaders > 1) {
         const int KT = K >> 5;
         if (sg.sync_before && L > 0 && !(p.lora && sg.lora_shrink)) {
-          if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) *p.status = 1;
+          if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
         }
         load_input(L, sg, KT, NS, chunks_of(NS, KT), nbuf_of(NS), nseq, 1);
         nseq += chunks_of(NS, KT);
@@ -1001,7 +1030,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             const int ms = c.l_ms[e < cnt ? e : 0];
             const int* f = p.tready + shrink_slot(sg, ms & 0xff, ms >> 8);
             while (!__all(e >= cnt || ld_agent(f) == lvl_tag)) {
-              if (++spins >= kSpinLimit) { *p.status = 1; break; }
+              if (++spins >= p.spin_limit) give_up(p.status);
               __builtin_amdgcn_s_sleep(2);
             }
           }
@@ -1163,7 +1192,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
   auto spin_until = [&](auto cond) __attribute__((always_inline)) {
     int spins = 0;
     while (!cond()) {
-      if (++spins >= kSpinLimit) { *p.status = 1; break; }
+      if (++spins >= p.spin_limit) give_up(p.status);
       __builtin_amdgcn_s_sleep(1);
     }
     compiler_fence();
@@ -1381,9 +1410,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     } else if (w == kLoader) {
       // ===================================== input loader =====================================
       if (sg.sync_before && L > 0) {
-        if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) {
-          *p.status = 1;
-        }
+        if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
       }
       const unsigned char* const Xb = reinterpret_cast<const unsigned char*>(sg.X);
       const bool xpk = sg.x_packed != 0;
@@ -1434,9 +1461,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
       // ===================================== LoRA wave: the level's shrinks =====================================
       if (p.lora) {
         if (sg.sync_before && L > 0) {
-          if (!grid_wait(p.flags, G, epoch * 16 + L, lane)) {
-            *p.status = 1;
-          }
+          if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
         }
         // the level's rows with a LoRA term, in row order (the same list in every workgroup); the loader wave may
         // still be drawing the previous level's items from the list when this level has no barrier before it
@@ -1772,11 +1797,15 @@ void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const
   p.n_stages = 0; p.M = M; p.Breq = Breq; p.ad = ad; p.tenant_id = tenant_id; p.route = route; p.row_to_req = row_to_req;
   p.lora = 1;
   p.tpart = ws.tpart; p.tfin = ws.tfin; p.tcount = ws.tcount; p.tready = ws.tready; p.nc_max = shrink_chunks(Kmax);
-  p.flags = ws.flags; p.status = ws.status;
+  p.flags = ws.flags; p.status = ws.status; p.spin_limit = g_wait_limit.load(std::memory_order_relaxed);
   p.wpart = ws.wpart; p.wss = ws.wss; p.segflag = ws.segflag; p.wsegs = 0;
 }
 
 }  // namespace
+
+int set_wait_limit(int polls) {
+  return g_wait_limit.exchange(polls > 0 ? polls : kSpinLimit, std::memory_order_relaxed);
+}
 
 size_t decode_packed_workspace_bytes(int M, int d, int F, int r_max) { return carve_decode_ws(nullptr, M, d, F, r_max, M > 32).bytes; }
 

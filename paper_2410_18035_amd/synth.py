@@ -52,6 +52,7 @@ class Workload:
     seed: int = 0
     sigma_w: float = 0.02
     sigma_lora: float = 0.02
+    sigma_router: float = 0.02  # router matrices and self-attention queries
 
     @property
     def torch_dtype(self):
@@ -63,14 +64,15 @@ CONFIGS = {
     "toy_fp32": Workload("toy_fp32", "f32", 256, 688, 1, 4, 4, (8,), (16, 16), decode_steps=8,
                          pool="mean", act="tanh", seed=0),
     "llama7b_layer_b32": Workload("llama7b_layer_b32", "bf16", 4096, 11008, 1, 32, 32, (32,), (256, 256),
-                                  decode_steps=64, pool="mean", act="gelu", seed=1),
+                                  decode_steps=64, pool="mean", act="gelu", seed=1, sigma_lora=0.08),
     "llama7b_stack_b64": Workload("llama7b_stack_b64", "bf16", 4096, 11008, 32, 64, 64, (32,), (128, 1024),
-                                  decode_steps=128, pool="mean", act="gelu", rmsnorm=True, tenants="uniform", seed=2),
+                                  decode_steps=128, pool="mean", act="gelu", rmsnorm=True, tenants="uniform", seed=2,
+                                  sigma_lora=0.08),
     "llama7b_prefill_b16": Workload("llama7b_prefill_b16", "bf16", 4096, 11008, 1, 16, 16, (32,), (1024, 2048),
-                                    pad_to=2048, pool="mean", act="gelu", seed=3),
+                                    pad_to=2048, pool="mean", act="gelu", seed=3, sigma_lora=0.08),
     "llama13b_stack_b128": Workload("llama13b_stack_b128", "bf16", 5120, 13824, 40, 128, 128, (8, 16, 64),
                                     (128, 1024), decode_steps=32, rmsnorm=True, tenants="permutation",
-                                    route_skew=(0.08, 0.08, 0.08, 0.08, 0.08, 0.30, 0.30), seed=4),
+                                    route_skew=(0.08, 0.08, 0.08, 0.08, 0.08, 0.30, 0.30), seed=4, sigma_lora=0.12),
 }
 
 _KIND = {"base": 1, "A": 2, "B": 3, "router": 4, "prompt": 5, "decode": 6, "tenant": 7, "rank": 8, "len": 9,
@@ -144,11 +146,11 @@ def adapters(wl: Workload, layer: int, device="cpu", zero_B: bool = False) -> La
 
 
 def router_weights(wl: Workload, layer: int, device="cpu") -> torch.Tensor:
-    return _normal((wl.T, NMOD, wl.d), wl.sigma_lora, wl, _gen(wl, "router", layer, 0, device), device)
+    return _normal((wl.T, NMOD, wl.d), wl.sigma_router, wl, _gen(wl, "router", layer, 0, device), device)
 
 
 def selfattn_query(wl: Workload, layer: int, device="cpu") -> torch.Tensor:
-    return _normal((wl.T, wl.d), wl.sigma_lora, wl, _gen(wl, "w_sa", layer, 0, device), device)
+    return _normal((wl.T, wl.d), wl.sigma_router, wl, _gen(wl, "w_sa", layer, 0, device), device)
 
 
 def prompt_lengths(wl: Workload) -> torch.Tensor:

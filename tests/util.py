@@ -42,3 +42,35 @@ def assert_routes_match(route_gpu: torch.Tensor, res: "oracle.RouteResult", dtyp
     bad = np.nonzero(keep & (got != res.route))[0]
     assert bad.size == 0, f"{what}: routes differ at requests {bad.tolist()} (gaps {res.gap[bad]}, sigma {sigma:.3g})"
     return 1.0 - keep.mean()
+
+
+def route_without_site(route: np.ndarray, site: int) -> np.ndarray:
+    """The route bytes with `site` taken out of every request's choice (a request left with nothing gets 255)."""
+    out = route.copy()
+    for b, v in enumerate(route):
+        v = int(v)
+        if v == site:
+            out[b] = 255
+        elif v != 255 and (v & 0x80) and (v >> site) & 1:
+            rest = (v & 0x7F) & ~(1 << site)
+            out[b] = (0x80 | rest) if rest else 255
+    return out
+
+
+def lora_visibility(run_oracle, route: np.ndarray, ref_outputs) -> float:
+    """How far the outputs move when the LoRA term of one site is dropped, at worst: for every site some
+    request uses, the oracle runs again without that site's term, and every request that used it must see
+    its outputs change; returns the smallest such change, as the row metric of the tolerances
+    (max_j |difference| / max_j |reference|, the larger of the outputs counts).  A parity tolerance far below
+    this number cannot be met by a kernel that loses a term."""
+    worst = np.inf
+    for site in range(7):
+        rows = np.array([b for b, v in enumerate(route) if oracle.route_has(int(v), site)], dtype=np.int64)
+        if rows.size == 0:
+            continue
+        dropped = run_oracle(route_without_site(route, site))
+        moved = np.zeros(rows.size)
+        for full, part in zip(ref_outputs, dropped):
+            moved = np.maximum(moved, row_rel_err(part[rows], full[rows]))
+        worst = min(worst, float(moved.min()))
+    return worst
