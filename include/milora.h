@@ -49,6 +49,7 @@ extern "C" {
  * every chosen site m (top-k with 1 < k < 7; the chosen sites' terms are added without weights: the
  * gate of Eq. 3 is not connected to Eq. 1 in the paper); MILORA_ROUTE_NONE = no LoRA term. */
 #define MILORA_ROUTE_SET 0x80
+#define MILORA_NOALLOC_SCRATCH_BYTES (8u << 20) /* scratch milora_layer_decode_noalloc holds on every GPU it runs on */
 
 typedef enum {
   MILORA_OK = 0,
@@ -209,6 +210,28 @@ int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
                         size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * milora_layer_decode_noalloc - milora_layer_decode for callers that can neither allocate device memory nor
+ * hand over a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and glue as milora_layer_decode without `workspace`; the scratch memory is an array
+ * of MILORA_NOALLOC_SCRATCH_BYTES inside the library's code object, which every GPU the entry point runs on
+ * holds from the library's first use there until the process ends.  The call allocates and frees nothing and
+ * enqueues a small fill kernel (the control words of the scratch start from zero in every call) and the decode
+ * launch on `stream`.
+ * Limits: packed bf16 weights only (anything else: EUNSUPPORTED, with the alignment rules of
+ * milora_layer_decode); B <= 32, and d, F, r_max such that the packed path's scratch fits the array - every
+ * LLaMA-2 shape up to d = 8192, F = 28672 with r_max <= 64, and the 7B and 13B shapes with any accepted rank
+ * (beyond: ERANGE).
+ * All calls on one GPU share that GPU's array: they must be ordered on one stream (or otherwise not overlap),
+ * calls that overlap race.  milora_packed_workspace_status(NULL, ...) reads the array's status word, which tells
+ * about the most recent call only.
+ * Errors: EINVAL, ERANGE, EUNSUPPORTED, EHIP.
+ */
+int milora_layer_decode_noalloc(const void *x, int B, int d, int F, int dtype,
+                                const milora_layer_weights *weights, const milora_adapters *adapters,
+                                const int32_t *tenant_id, const uint8_t *route, uint32_t flags,
+                                const void *attn_out, void *y, void *qkv_out, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * milora_packed_workspace_status - the packed-weight kernels (milora_layer_decode and milora_routed_linear
  * with MILORA_W_PACKED) run as ONE launch of one workgroup per compute unit whose workgroups hand data to each
  * other inside the launch (the four dependent levels of a layer step) and wait for it with bounded polls.
@@ -219,7 +242,8 @@ int milora_layer_decode(const void *x, int B, int d, int F, int dtype,
  * to 1 and ends, the waves that depend on it run out the same way, and the launch finishes with wrong or
  * missing results instead of hanging.  This call waits for the work queued on `stream`, then copies that word
  * to *status (host): 0 = every wait ended normally since the workspace was zero-filled.  After a 1 the
- * workspace must be zero-filled again before its next use.
+ * workspace must be zero-filled again before its next use.  workspace == NULL: the word of the scratch array
+ * of milora_layer_decode_noalloc on the current GPU.
  * Errors: EINVAL, EHIP.
  */
 int milora_packed_workspace_status(const void *workspace, int *status, void *stream);

@@ -32,7 +32,8 @@ EXPORTS = (
     "milora_version", "milora_status_string", "milora_last_hip_error",
     "milora_route_workspace_bytes", "milora_route",
     "milora_routed_linear_workspace_bytes", "milora_routed_linear_kernel", "milora_routed_linear",
-    "milora_layer_decode_workspace_bytes", "milora_layer_decode", "milora_layer_decode_profile",
+    "milora_layer_decode_workspace_bytes", "milora_layer_decode", "milora_layer_decode_noalloc",
+    "milora_layer_decode_profile",
     "milora_pack_weight", "milora_packed_workspace_status", "milora_set_wait_limit",
     "milora_measure_workspace_bytes", "milora_measure_matrix_rate", "milora_measure_read_rate",
 )
@@ -86,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.milora_layer_decode.restype = i32
         L.milora_layer_decode.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(_LayerWeights),
                                           ctypes.POINTER(_Adapters), vp, vp, ctypes.c_uint32, vp, vp, vp, vp, sz, vp]
+        L.milora_layer_decode_noalloc.restype = i32
+        L.milora_layer_decode_noalloc.argtypes = L.milora_layer_decode.argtypes[:13] + [vp]
         L.milora_layer_decode_profile.restype = i32
         L.milora_layer_decode_profile.argtypes = L.milora_layer_decode.argtypes + [i32, ctypes.POINTER(ctypes.c_float)]
         L.milora_pack_weight.restype = i32
@@ -306,6 +309,26 @@ def milora_layer_decode(x: torch.Tensor, weights: Sequence[torch.Tensor], adapte
     return y, qkv_out
 
 
+def milora_layer_decode_noalloc(x: torch.Tensor, weights: Sequence[torch.Tensor], adapters: AdapterTable,
+                                tenant_id: torch.Tensor, route: torch.Tensor, F: int, y: torch.Tensor,
+                                qkv_out: Optional[torch.Tensor] = None, rmsnorm: bool = False,
+                                attn_out: Optional[torch.Tensor] = None) -> None:
+    """milora_layer_decode on the library's own scratch array (packed bf16 weights, B <= 32): the caller passes
+    every buffer, nothing is allocated here or in the library."""
+    B, d = x.shape
+    lw = _LayerWeights()
+    for m, w in enumerate(weights):
+        lw.W[m] = _dev(w, x.dtype)
+    lw.layout = W_PACKED
+    ad = adapters.c_struct()
+    rc = lib().milora_layer_decode_noalloc(_dev(x), B, d, F, _dtype_code(x), ctypes.byref(lw), ctypes.byref(ad),
+                                           _dev(tenant_id, torch.int32), _dev(route, torch.uint8),
+                                           LAYER_RMSNORM if rmsnorm else 0, _dev(attn_out, x.dtype), _dev(y),
+                                           _dev(qkv_out), _stream())
+    if rc != 0:
+        raise MiloraError(rc, "milora_layer_decode_noalloc")
+
+
 def milora_pack_weight(W: torch.Tensor) -> torch.Tensor:
     """One-time re-ordering of a row-major bf16 [d2, d1] weight into the packed decode layout."""
     d2, d1 = W.shape
@@ -342,8 +365,9 @@ def milora_set_wait_limit(polls: int) -> int:
     return int(lib().milora_set_wait_limit(int(polls)))
 
 
-def milora_packed_workspace_status(workspace: torch.Tensor) -> int:
-    """0 unless a bounded wait inside a packed-weight launch on this workspace ran out (waits for the stream)."""
+def milora_packed_workspace_status(workspace: Optional[torch.Tensor]) -> int:
+    """0 unless a bounded wait inside a packed-weight launch on this workspace ran out (waits for the stream).
+    None: the scratch array of milora_layer_decode_noalloc on the current GPU."""
     out = ctypes.c_int(-1)
     rc = lib().milora_packed_workspace_status(_dev(workspace), ctypes.byref(out), _stream())
     if rc:

@@ -18,6 +18,10 @@ int routed_linear_packed(const bf16_t* X, int M, int d1, int d2, const int32_t* 
 size_t routed_linear_packed_workspace_bytes(int M, int d1, int d2, int r_max);
 int pack_weight(const void* src, void* dst, int d1, int d2, hipStream_t st);
 int set_wait_limit(int polls);
+int layer_decode_packed_static(const bf16_t* x, int B, int d, int F, const milora_layer_weights* wts, const AdapterView& ad,
+                               const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
+                               bf16_t* y, bf16_t* qkv_out, hipStream_t st);
+int static_scratch_status(int* status, hipStream_t st);
 // prefill.hip
 int decode_workspace_status(const void* workspace, int* status, hipStream_t st);
 bool prefill_supported(int64_t M, int d1, int d2, const void* X, const void* W, const void* Y);
@@ -275,7 +279,8 @@ extern "C" int milora_routed_linear(const void* X, int64_t M, int d1, int d2, in
 }
 
 extern "C" int milora_packed_workspace_status(const void* workspace, int* status, void* stream) {
-  if (!workspace || !status) return MILORA_EINVAL;
+  if (!status) return MILORA_EINVAL;
+  if (!workspace) return static_scratch_status(status, (hipStream_t)stream);
   return decode_workspace_status(workspace, status, (hipStream_t)stream);
 }
 
@@ -328,6 +333,26 @@ extern "C" int milora_layer_decode(const void* x, int B, int d, int F, int dtype
                                    size_t workspace_bytes, void* stream) {
   return layer_decode_impl(x, B, d, F, dtype, weights, adapters, tenant_id, route, flags, attn_out, y, qkv_out,
                            workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int milora_layer_decode_noalloc(const void* x, int B, int d, int F, int dtype,
+                                           const milora_layer_weights* weights, const milora_adapters* adapters,
+                                           const int32_t* tenant_id, const uint8_t* route, uint32_t flags,
+                                           const void* attn_out, void* y, void* qkv_out, void* stream) {
+  if (!x || !y || !weights || !tenant_id || !route) return MILORA_EINVAL;
+  if (B < 1 || d < 1 || F < 1 || !valid_dtype(dtype)) return MILORA_EINVAL;
+  if (flags & ~MILORA_LAYER_RMSNORM) return MILORA_EINVAL;
+  for (int m = 0; m < MILORA_NUM_SITES; ++m)
+    if (!weights->W[m]) return MILORA_EINVAL;
+  int rc = check_adapters(adapters);
+  if (rc) return rc;
+  if (weights->layout != MILORA_W_PACKED || dtype != MILORA_BF16 || d % 32 != 0 || F % 32 != 0) return MILORA_EUNSUPPORTED;
+  if (!aligned16(x) || (attn_out && !aligned16(attn_out)) || !aligned16(y) || (qkv_out && !aligned16(qkv_out)))
+    return MILORA_EUNSUPPORTED;
+  for (int m = 0; m < MILORA_NUM_SITES; ++m)
+    if (!aligned16(weights->W[m])) return MILORA_EUNSUPPORTED;
+  return layer_decode_packed_static((const bf16_t*)x, B, d, F, weights, view_of(adapters), tenant_id, route, flags,
+                                    (const bf16_t*)attn_out, (bf16_t*)y, (bf16_t*)qkv_out, (hipStream_t)stream);
 }
 
 extern "C" int milora_layer_decode_profile(const void* x, int B, int d, int F, int dtype,

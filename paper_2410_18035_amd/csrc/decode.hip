@@ -21,6 +21,7 @@
 // grid barrier of per-workgroup flags (monotone values, nothing to reset between launches).
 // All sums run in a fixed order: results do not depend on timing.
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -1900,6 +1901,68 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
   if (rc) return rc;
   if (marks && marks->n > 0) (void)hipEventRecord(marks->ev[0], st);
   return MILORA_OK;
+}
+
+// ---- layer decode on scratch memory the library itself holds ----------------------------------------------------
+// For callers that can neither allocate nor hand over a workspace.  The array lives in every GPU the library runs
+// on, from the first use of the library on it to the end of the process; each GPU has its own copy at its own
+// address, looked up once per device.  In host code the array's name is only a handle for that lookup: what the
+// kernels get is the looked-up address.
+constexpr size_t kStaticScratchBytes = (size_t)MILORA_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  MILORA_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return MILORA_ERANGE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    MILORA_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return hip_fail(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return MILORA_OK;
+}
+
+__global__ void __launch_bounds__(256) clear_words_kernel(uint32_t* __restrict__ p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// Bytes at the start of a decode workspace that must read zero before its first launch: barrier flags, status word,
+// shrink counters and ready words.
+static size_t control_bytes() {
+  static char base;
+  const DecodeWs ws = carve_decode_ws(&base, 1, 32, 32, 1);
+  return (size_t)((const char*)ws.tfin - &base);
+}
+
+int layer_decode_packed_static(const bf16_t* x, int B, int d, int F, const milora_layer_weights* wts, const AdapterView& ad,
+                               const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
+                               bf16_t* y, bf16_t* qkv_out, hipStream_t st) {
+  if (B > 32) return MILORA_ERANGE;  // more rows take the kernel whose partial-tile tables need tens of MB
+  if (carve_decode_ws(nullptr, B, d, F, ad.r_max, false).bytes > kStaticScratchBytes) return MILORA_ERANGE;
+  void* ptr = nullptr;
+  int rc = static_scratch(&ptr);
+  if (rc) return rc;
+  // The array keeps what the last call left, and that call may have had other sizes or may have run out of a wait:
+  // the control words start from zero in every call (a fill kernel, so that the call can be captured in a graph).
+  const int words = (int)(control_bytes() / sizeof(uint32_t));
+  hipLaunchKernelGGL(clear_words_kernel, dim3((words + 255) / 256), dim3(256), 0, st, (uint32_t*)ptr, words);
+  if ((rc = check_launch())) return rc;
+  return layer_decode_packed(x, B, d, F, wts, ad, tenant_id, route, flags, attn_out, y, qkv_out, ptr, st, nullptr);
+}
+
+int static_scratch_status(int* status, hipStream_t st) {
+  void* ptr = nullptr;
+  int rc = static_scratch(&ptr);
+  if (rc) return rc;
+  return decode_workspace_status(ptr, status, st);
 }
 
 // ---- one routed linear of M <= 128 rows on a packed weight ------------------------------------------
