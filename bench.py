@@ -48,6 +48,41 @@ def measured_traffic(workload):
     return None
 
 
+STREAM_PHASES = {  # (waves, slot) of milora_layer_decode_trace's stamps, few-row kernel
+    "stream_first_input": (range(0, 6), 1), "stream_matrix_work_done": (range(0, 6), 2), "stream_tiles_summed": (range(0, 6), 3),
+    "loader_barrier_passed": ([6], 1), "loader_first_chunk": ([6], 2), "loader_all_chunks": ([6], 3),
+    "loader_outputs_stored": ([6], 5), "lora_shrink_items_done": ([7], 2), "lora_shrinks_published": ([7], 3),
+    "lora_expands_formed": ([7], 4), "lora_outputs_stored": ([7], 6), "flag_stored": ([7], 7)}
+WIDE_PHASES = {
+    "level_entered": (range(0, 8), 0), "stream_first_input": (range(0, 6), 1), "stream_segments_stored": (range(0, 6), 2),
+    "loader_barrier_passed": ([6], 1), "loader_copies_landed": ([6], 2), "lora_list_built": ([7], 2),
+    "lora_wave_shrink_items_done": ([7], 6), "lora_wave_expand_items_done": ([7], 3),
+    "loader_shrink_items_done": ([6], 6), "loader_expand_items_done": ([6], 3),
+    "lora_wave_item1_begun": ([7], 8), "lora_wave_item1_sums_done": ([7], 9), "lora_wave_item1_stores_acked": ([7], 10),
+    "lora_wave_item1_counted": ([7], 11), "lora_wave_item1_published": ([7], 12),
+    "sums_begun": (range(0, 8), 4), "sums_stored": (range(0, 8), 5)}
+
+
+def phase_table(np, stamps, wide):
+    """Per stage and phase: the time (us after the launch's first stamp) by which half of the workgroups, and the
+    last one, have reached it; a workgroup reaches a phase when the last of the waves that have it does."""
+    t = stamps.numpy().astype(np.float64)
+    t0 = t[t > 0].min()
+    out = {}
+    for L in range(t.shape[1]):
+        row = {}
+        for name, (waves, slot) in (WIDE_PHASES if wide else STREAM_PHASES).items():
+            v = t[:, L, list(waves), slot]
+            v = np.where(v > 0, v - t0, np.nan)
+            if np.isnan(v).all():
+                continue
+            per_wg = np.nanmax(v, axis=1) * 0.01
+            per_wg = per_wg[~np.isnan(per_wg)]
+            row[name] = [round(float(np.median(per_wg)), 2), round(float(per_wg.max()), 2)]
+        out[f"stage{L}"] = row
+    return out
+
+
 def algorithmic_bytes(wl, routes, tenant_ids, ranks):
     """Bytes the method itself must move for one decode layer-step, and for the gate/up launch alone.
 
@@ -255,6 +290,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0,
                     help="single-layer workloads: run the layer with this many requests (and as many tenants) "
                          "instead of the workload's own batch, e.g. 64 or 128 on llama7b_layer_b32")
+    ap.add_argument("--phases", action="store_true",
+                    help="single-layer workloads: also run one decode step on the tracing build of the kernel and "
+                         "report when the workgroups reach each phase of each stage (median, last; us)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the many-row (prefill configuration) leg")
@@ -372,6 +410,12 @@ def main():
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name),
                 "algorithmic_bytes_per_launch": nbytes["layer_step"], "avg_launch_ms": round(dominant_ms, 5)}
 
+    phases = None
+    if args.phases:
+        for _ in range(3):
+            stamps = mb.milora_layer_decode_trace(xs[0], Wp, tab, tid, route, wl.F, ys[0], qkv, ws_layer, rmsnorm=wl.rmsnorm)
+        phases = phase_table(np, stamps, wl.B > 32)
+
     # ---- the oracle on the host cores, bounded sample ---------------------------------------------
     cpu, parity = None, None
     if not args.no_cpu_baseline:
@@ -438,6 +482,8 @@ def main():
                        "route_call_us": round(route_ms * 1e3, 2)},
         "tokens_per_s_32_layer_equivalent_extrapolated": round(value / 32, 1),
     }
+    if phases is not None:
+        out["phases_us_median_and_last_workgroup"] = phases
     print(json.dumps(out))
 
 

@@ -270,6 +270,31 @@ int milora_layer_decode_profile(const void *x, int B, int d, int F, int dtype,
                                 size_t workspace_bytes, void *stream, int reps, float *slot_ms);
 
 /* ------------------------------------------------------------------------------------------------
+ * milora_layer_decode_trace - measurement aid, not part of the method: one milora_layer_decode (packed weights
+ * only) on an instantiation of the decode kernel in which every wave writes time stamps (the GPU's 100 MHz
+ * constant clock) at the boundaries of its phases in every stage, then a synchronisation.  Same arguments, results
+ * and errors as milora_layer_decode, plus:
+ *   stamps        device, milora_layer_decode_trace_bytes() bytes: int64 [workgroup][dims[2]][dims[3]][dims[4]],
+ *                 zero where a wave has no such phase; cleared by the call
+ *   dims          HOST int32 [5]: workgroups and stages of the launch, then the three array extents above
+ * Stamp slots, few-row kernel (waves 0..5 stream, 6 loader, 7 LoRA): stream 0 stage entered, 1 first input chunk
+ * there, 2 matrix work done, 3 partial tiles summed; loader 0 entered, 1 grid barrier passed, 2 first chunk landed,
+ * 3 all landed, 4 sums complete with LoRA terms, 5 own outputs stored; LoRA 0 entered, 1 barrier passed, 2 shrink
+ * items done, 3 shrinks of own rows published, 4 expands formed, 5 stream waves' sums there, 6 own outputs stored,
+ * 7 hand-over flag stored.  Many-row kernel: all 0 level entered, 4 sums begun, 5 own sums stored; stream 1 first
+ * chunk there, 2 segments stored; loader 1 barrier passed, 2 copies landed, 3 shrink items done; LoRA 1 barrier
+ * passed, 2 shrink list built, 3 shrink items done.
+ * Errors: those of milora_layer_decode; EUNSUPPORTED for other layouts; EWORKSPACE for a short `stamps`.
+ */
+size_t milora_layer_decode_trace_bytes(void);
+int milora_layer_decode_trace(const void *x, int B, int d, int F, int dtype,
+                              const milora_layer_weights *weights, const milora_adapters *adapters,
+                              const int32_t *tenant_id, const uint8_t *route, uint32_t flags,
+                              const void *attn_out, void *y, void *qkv_out, void *workspace,
+                              size_t workspace_bytes, void *stream, void *stamps, size_t stamps_bytes,
+                              int32_t *dims);
+
+/* ------------------------------------------------------------------------------------------------
  * milora_pack_weight - one-time re-ordering of a bf16 base weight from MILORA_W_ROWMAJOR to
  * MILORA_W_PACKED (see milora_wlayout), so that the decode kernels stream it with fully
  * coalesced 1 KiB loads already in matrix-core operand order.  src and dst: device, d1*d2

@@ -33,7 +33,7 @@ EXPORTS = (
     "milora_route_workspace_bytes", "milora_route",
     "milora_routed_linear_workspace_bytes", "milora_routed_linear_kernel", "milora_routed_linear",
     "milora_layer_decode_workspace_bytes", "milora_layer_decode", "milora_layer_decode_noalloc",
-    "milora_layer_decode_profile",
+    "milora_layer_decode_profile", "milora_layer_decode_trace_bytes", "milora_layer_decode_trace",
     "milora_pack_weight", "milora_packed_workspace_status", "milora_set_wait_limit",
     "milora_measure_workspace_bytes", "milora_measure_matrix_rate", "milora_measure_read_rate",
 )
@@ -91,6 +91,10 @@ def lib() -> ctypes.CDLL:
         L.milora_layer_decode_noalloc.argtypes = L.milora_layer_decode.argtypes[:13] + [vp]
         L.milora_layer_decode_profile.restype = i32
         L.milora_layer_decode_profile.argtypes = L.milora_layer_decode.argtypes + [i32, ctypes.POINTER(ctypes.c_float)]
+        L.milora_layer_decode_trace_bytes.restype = sz
+        L.milora_layer_decode_trace_bytes.argtypes = []
+        L.milora_layer_decode_trace.restype = i32
+        L.milora_layer_decode_trace.argtypes = L.milora_layer_decode.argtypes + [vp, sz, ctypes.POINTER(ctypes.c_int32)]
         L.milora_pack_weight.restype = i32
         L.milora_pack_weight.argtypes = [vp, vp, i32, i32, vp]
         L.milora_packed_workspace_status.restype = i32
@@ -307,6 +311,31 @@ def milora_layer_decode(x: torch.Tensor, weights: Sequence[torch.Tensor], adapte
     if rc != 0:
         raise MiloraError(rc, "milora_layer_decode")
     return y, qkv_out
+
+
+def milora_layer_decode_trace(x: torch.Tensor, weights: Sequence[torch.Tensor], adapters: AdapterTable,
+                              tenant_id: torch.Tensor, route: torch.Tensor, F: int, y: torch.Tensor,
+                              qkv_out: Optional[torch.Tensor], workspace: torch.Tensor, rmsnorm: bool = False,
+                              attn_out: Optional[torch.Tensor] = None):
+    """One traced decode step on packed weights; returns (stamps int64 [G, stages, waves, slots] on the host in
+    units of 10 ns, 0 = not written)."""
+    B, d = x.shape
+    lw = _LayerWeights()
+    for m, w in enumerate(weights):
+        lw.W[m] = _dev(w, x.dtype)
+    lw.layout = W_PACKED
+    ad = adapters.c_struct()
+    nbytes = int(lib().milora_layer_decode_trace_bytes())
+    stamps = torch.empty(nbytes // 8, dtype=torch.int64, device=x.device)
+    dims = (ctypes.c_int32 * 5)()
+    rc = lib().milora_layer_decode_trace(_dev(x), B, d, F, _dtype_code(x), ctypes.byref(lw), ctypes.byref(ad),
+                                         _dev(tenant_id, torch.int32), _dev(route, torch.uint8),
+                                         LAYER_RMSNORM if rmsnorm else 0, _dev(attn_out, x.dtype), _dev(y), _dev(qkv_out),
+                                         _dev(workspace), workspace.numel(), _stream(), _dev(stamps), nbytes, dims)
+    if rc != 0:
+        raise MiloraError(rc, "milora_layer_decode_trace")
+    G, stages, smax, waves, slots = (int(v) for v in dims)
+    return stamps.cpu().view(-1, smax, waves, slots)[:G, :stages]
 
 
 def milora_layer_decode_noalloc(x: torch.Tensor, weights: Sequence[torch.Tensor], adapters: AdapterTable,

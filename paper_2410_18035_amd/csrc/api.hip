@@ -18,6 +18,8 @@ int routed_linear_packed(const bf16_t* X, int M, int d1, int d2, const int32_t* 
 size_t routed_linear_packed_workspace_bytes(int M, int d1, int d2, int r_max);
 int pack_weight(const void* src, void* dst, int d1, int d2, hipStream_t st);
 int set_wait_limit(int polls);
+size_t decode_trace_bytes();
+int decode_trace_dims(int* stages_max, int* waves, int* slots);
 int layer_decode_packed_static(const bf16_t* x, int B, int d, int F, const milora_layer_weights* wts, const AdapterView& ad,
                                const int32_t* tenant_id, const uint8_t* route, uint32_t flags, const bf16_t* attn_out,
                                bf16_t* y, bf16_t* qkv_out, hipStream_t st);
@@ -381,6 +383,31 @@ extern "C" int milora_layer_decode_profile(const void* x, int B, int d, int F, i
   }
   for (int i = 0; i <= MILORA_PROFILE_SLOTS; ++i) (void)hipEventDestroy(ev[i]);
   return rc;
+}
+
+extern "C" size_t milora_layer_decode_trace_bytes(void) { return decode_trace_bytes(); }
+
+extern "C" int milora_layer_decode_trace(const void* x, int B, int d, int F, int dtype,
+                                         const milora_layer_weights* weights, const milora_adapters* adapters,
+                                         const int32_t* tenant_id, const uint8_t* route, uint32_t flags,
+                                         const void* attn_out, void* y, void* qkv_out, void* workspace,
+                                         size_t workspace_bytes, void* stream, void* stamps, size_t stamps_bytes,
+                                         int32_t* dims) {
+  if (!stamps || !dims) return MILORA_EINVAL;
+  if (stamps_bytes < decode_trace_bytes()) return MILORA_EWORKSPACE;
+  if (!weights || weights->layout != MILORA_W_PACKED) return MILORA_EUNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  MILORA_HIP(hipMemsetAsync(stamps, 0, decode_trace_bytes(), st));
+  LaunchMarks marks{nullptr, 0};
+  marks.trace = (long long*)stamps;
+  const int rc = layer_decode_impl(x, B, d, F, dtype, weights, adapters, tenant_id, route, flags, attn_out, y, qkv_out,
+                                   workspace, workspace_bytes, stream, &marks);
+  if (rc != MILORA_OK) return rc;
+  MILORA_HIP(hipStreamSynchronize(st));
+  int smax = 0, waves = 0, slots = 0;
+  decode_trace_dims(&smax, &waves, &slots);
+  dims[0] = marks.grid; dims[1] = marks.stages; dims[2] = smax; dims[3] = waves; dims[4] = slots;
+  return MILORA_OK;
 }
 
 extern "C" int milora_pack_weight(const void* src_rowmajor, void* dst_packed, int d1, int d2, void* stream) {

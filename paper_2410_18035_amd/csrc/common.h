@@ -104,6 +104,8 @@ __device__ __forceinline__ int routed_rank(const AdapterView& ad, const int32_t*
 struct LaunchMarks {
   hipEvent_t* ev;
   int n;
+  long long* trace = nullptr;  // device buffer for the kernels' own time stamps (tracing launch), or null
+  int grid = 0, stages = 0;    // filled in by a tracing launch: workgroups and stages it ran
 };
 
 // The many-row LoRA shrink cuts its reduction into this many parts (one workgroup each); the workspace holds

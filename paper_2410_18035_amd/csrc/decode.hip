@@ -52,6 +52,7 @@ constexpr int kSteady = 8;              // weight loads per stream wave in fligh
 constexpr int kSpinLimit = 1 << 22;     // polls before a bounded wait gives up (unless the caller set another limit)
 constexpr int kCtrlBytes = 12288;       // control block at the start of LDS
 constexpr int kLdsBytes = 160 * 1024;       // all of a compute unit's LDS: one workgroup per unit
+constexpr int kTraceSlots = 16;             // time stamps per (workgroup, stage, wave) of a tracing launch
 
 // Per row-tile-count tuning: ring depth, tiles per workgroup and stage, stream waves that share a partial-tile
 // area at a stage end, bytes of LDS for LoRA expands formed ahead of the stage end.
@@ -103,9 +104,15 @@ struct Params {
   float* wss;     // wide kernel: [segments][rows] sums of squares of the input rows over the segment
   int* segflag;   // wide kernel: [segments] launch epoch * 16 + level of the segment stored there
   int wsegs;      // wide kernel: segments per table half (even levels use the first half of the three tables, odd the second)
+  int* tpflag;    // wide kernel: [slots][kTpStride] launch epoch * 16 + level + 1 of the shrink partial of each k chunk
+  float* delta;   // wide kernel: LoRA terms t W^B as fp32 tiles [site tile][row tile][256], laid out like the partial tiles;
+                  // tiles of even levels first, those of odd levels from tile delta_odd on
+  int* dready;    // wide kernel: [level parity][site position][slab of 256 columns][row] tag of the LoRA term stored there
+  int delta_odd, slabs_max;
   int* flags;     // [kMaxGrid] grid barrier flags, monotone
   int* status;    // set to 1 when a bounded wait ran out
   int spin_limit; // polls before a bounded wait gives up
+  long long* trace;  // tracing launches only: [workgroup][stage][wave][8] time stamps (100 MHz clock), see TS
   Stage st[kMaxStages];
 };
 
@@ -128,6 +135,7 @@ struct Ctrl {
   int lvl_arr[kMaxStages];  // wide kernel: waves that have finished the level (a wave with nothing to do in a level runs ahead)
   int shr_next[kMaxStages];  // wide kernel: shrink items of a level handed out so far (the LoRA and loader waves draw from it)
   int shr_ready;   // wide kernel: levels whose shrink list stands in s_rows
+  int exp_next[kMaxStages];  // wide kernel: expand items of a level handed out so far
   int s_flag;
   float ss_part[kSW][kMaxRows];
   float inv_rows[kMaxRows];
@@ -145,6 +153,7 @@ static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
 // follow q,k,v without one (attention output supplied by the caller), and with several sites per request a row
 // can have a LoRA term in both.
 constexpr int kSlotsPerRow = 4;
+constexpr int kTpStride = 64;  // flag words per shrink slot: one per k chunk (reductions of up to 64 * kShrinkChunk)
 __device__ __host__ __forceinline__ int shrink_slot(const Stage& sg, int m, int pos) { return m * kSlotsPerRow + sg.tpos0 + pos; }
 
 // ---- memory-model helpers ---------------------------------------------------------------------------
@@ -222,6 +231,12 @@ __device__ __forceinline__ float sumsq8(u32x4 v) {
 
 __host__ __device__ __forceinline__ int shrink_chunks(int K) { return (K + kShrinkChunk - 1) / kShrinkChunk; }
 
+// Time stamp `slot` of this wave in stage L; compiled in only for the tracing instantiation of a kernel.
+#define TS(slot)                                                                                              \
+  do {                                                                                                        \
+    if (TRACE && lane == 0) p.trace[(((size_t)wg * kMaxStages + L) * kWaves + w) * kTraceSlots + (slot)] = wall_clock64(); \
+  } while (0)
+
 
 // A bounded wait ran out (another launch holds compute units this one needs, or a fault elsewhere): record it and
 // end this wave.  What it waited for never came, so nothing it would do next has its inputs; the waves and
@@ -251,9 +266,9 @@ __device__ __forceinline__ bool grid_wait(const int* flags, int G, int target, i
 }
 
 // ---- one LoRA shrink item by one wave: partial t of row m over one k chunk ---------------------------
-template <int MT>
+template <int MT, bool PER_CHUNK = false, int BATCH = 32>
 __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& sg, int m, int pos, int tenant, int r,
-                                                 int kc, int NC, int tag, int lane) {
+                                                 int kc, int NC, int tag, int lane, long long* ts = nullptr) {
   const int site = sg.site[pos], slot = shrink_slot(sg, m, pos);
   const gbf16* A = (const gbf16*)p.ad.A[tenant * MILORA_NUM_SITES + site];
   const int K = sg.K, rmax = p.ad.r_max;
@@ -276,16 +291,16 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
     for (int v = 0; v < 8; ++v) acc[v] = 0.f;
     const gu32x4* Ap = reinterpret_cast<const gu32x4*>(A) + cg;
     int k = k_lo + kr;
-    for (; k + 31 * kpl < k_hi; k += 32 * kpl) {  // rank 32: the whole chunk in one round trip
-      u32x4 a[32];
-      float x[32];
+    for (; k + (BATCH - 1) * kpl < k_hi; k += BATCH * kpl) {  // rank 32, BATCH 32: the whole chunk in one round trip
+      u32x4 a[BATCH];
+      float x[BATCH];
 #pragma unroll
-      for (int u = 0; u < 32; ++u) {
+      for (int u = 0; u < BATCH; ++u) {
         a[u] = __builtin_nontemporal_load(Ap + (size_t)(k + u * kpl) * lpr);
         x[u] = xval(k + u * kpl);
       }
 #pragma unroll
-      for (int u = 0; u < 32; ++u)
+      for (int u = 0; u < BATCH; ++u)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           acc[2 * v] += x[u] * __uint_as_float(a[u][v] << 16);
@@ -315,12 +330,19 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
       st_agent(out + c, acc);
     }
   }
+  if (ts && lane == 0) ts[0] = wall_clock64();  // loads and sums done, partial stores issued
+  wait_all_mem();
+  if (ts && lane == 0) ts[1] = wall_clock64();  // partial stores acknowledged
+  if (PER_CHUNK) {  // readers wait for the chunks' flags and add the partials themselves, in chunk order
+    st_agent(p.tpflag + slot * kTpStride + kc, tag);  // (every lane stores the same word: no one-lane region at the item's end)
+    return;
+  }
   // The wave that completes the row's last partial adds all of them in chunk order (whoever it is: the order
   // of the sum is fixed) and publishes t; every workgroup with a tile of the site reads it from there.
-  wait_all_mem();
   int done = 0;
   if (lane == 0) done = __hip_atomic_fetch_add(&p.tcount[slot], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
   done = __builtin_amdgcn_readfirstlane(done);
+  if (ts && lane == 0) ts[2] = wall_clock64();  // arrival counted
   if (done == NC) {
     for (int c = lane; c < r; c += 64) {
       const float* tp = row_part + c;
@@ -339,10 +361,11 @@ __device__ __forceinline__ void lora_shrink_item(const Params& p, const Stage& s
       st_agent(&p.tcount[slot], 0);
       st_agent(&p.tready[slot], tag);
     }
+    if (ts && lane == 0) ts[3] = wall_clock64();  // the row's shrink summed and published
   }
 }
 
-template <int MT>
+template <int MT, bool TRACE>
 __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p) {
   constexpr int D = Cfg<MT>::D, NSMAX = Cfg<MT>::NS, CHAIN = Cfg<MT>::CHAIN;
   constexpr int kSlots = kSW / CHAIN;                     // partial-tile areas of the stream waves at a stage end
@@ -543,6 +566,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
       const int NCH = chunks_of(NS, KT);
       const int NBUF = nbuf_of(NS);
+      TS(0);
 #pragma unroll
       for (int a = 0; a < NSMAX; ++a)
 #pragma unroll
@@ -588,6 +612,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
 #pragma unroll
                   for (int mt = 0; mt < MT; ++mt) xb[mt] = xn[mt];
                 }
+                if (TRACE && i == 0) TS(1);
                 // the chunk after it, if the loader is that far: its LDS reads overlap this k block's work
                 have_next = i + 1 < NCH && seen[(i + 1) % kLoaders] > lbase[(i + 1) % kLoaders] + (i + 1) / kLoaders;
                 if (have_next) {
@@ -634,6 +659,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
 #pragma unroll
               for (int mt = 0; mt < MT; ++mt) acc[t][mt] += acc[q][mt];
       }
+      TS(2);
       compiler_fence();
       st_lds(&c.x_done[w], nseq + NCH);
       nseq += NCH;
@@ -687,6 +713,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         if (lane == 0) __hip_atomic_fetch_add(&c.part_cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (lane == 0) __hip_atomic_fetch_add(&c.slot_turn[w / CHAIN], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
+      TS(3);
       if (lane == 0) __hip_atomic_fetch_add(&c.sum_cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     return;
@@ -930,11 +957,13 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             if (depth == kDepth) wait_vm<LPC * (kDepth - 1)>();
             else wait_vm<0>();
             lds_poke(ready_off, lcount + (depth == kDepth ? mine + 2 - depth : mine + 1));
+            if (TRACE && mine + 1 == depth) TS(2);
           }
         }
         wait_vm<0>();
         lcount += mine;
         lds_poke(ready_off, lcount);
+        TS(3);
       }
   };
 
@@ -950,17 +979,21 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
       const int NCH = chunks_of(NS, KT);
       const int NBUF = nbuf_of(NS);
+      TS(0);
       if (sg.sync_before && L > 0) {
         if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
       }
+      TS(1);
       load_input(L, sg, KT, NS, NCH, NBUF, nseq, 0);
       nseq += NCH;
       // ---- stage end: the LoRA wave has added the LoRA terms to the sums ---------------------------------------
       float pre[8];
       glue_prefetch(L, sg, NS, 0, pre);
       spin_until([&]() { return ld_lds(&c.tail_go) >= L + 1; });
+      TS(4);
       glue(L, sg, NS, 0, pre);
       wait_all_mem();
+      TS(5);
       st_lds(&c.tail_done, L + 1);
     }
   } else {
@@ -971,11 +1004,13 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       const int K = sg.K;
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
       const int NC = shrink_chunks(K);
+      TS(0);
       if (sg.lora_shrink) lvl_tag = epoch * 16 + L + 1;  // a slot can serve several levels of one launch
       if (p.lora && sg.lora_shrink) {
         if (sg.sync_before && L > 0) {
           if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
         }
+        TS(1);
         // the rows with a LoRA term at one of this level's sites, in row order (the same list in every workgroup)
         if (lane == 0) c.s_cnt = 0;
         wave_sync();
@@ -996,6 +1031,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
           const int ms = c.s_rows[it / NC], m = ms & 0xff;
           lora_shrink_item<MT>(p, sg, m, ms >> 8, c.r_ten[m], c.r_rank[m], it % NC, NC, lvl_tag, lane);
         }
+        TS(2);
       }
       if (kLoaders > 1) {
         const int KT = K >> 5;
@@ -1036,6 +1072,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             }
           }
         }
+        TS(3);
         const int cap_d = kDeltaBytes / (NS * 64), cap_t = kTBytes / (p.ad.r_max * 4);  // entries `delta` and t_lds hold
         npre = cnt < cap_d ? cnt : cap_d;
         npre = npre < cap_t ? npre : cap_t;
@@ -1047,11 +1084,13 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         wave_sync();
         expand(L, sg, NS, NC, 0, npre, false);
         wave_sync();
+        TS(4);
       }
       float pre[8];
       glue_prefetch(L, sg, NS, 1, pre);
       // ---- stage end: all six stream waves have summed their part of the tiles ---------------------------------
       spin_until([&]() { return ld_lds(&c.sum_cnt) >= (L + 1) * kSW; });
+      TS(5);
       for (int m = lane; m < MT * 16; m += 64) {
         float ssq = 0.f;
 #pragma unroll
@@ -1073,10 +1112,12 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       st_lds(&c.tail_go, L + 1);
       glue(L, sg, NS, 1, pre);
       wait_all_mem();
+      TS(6);
       spin_until([&]() { return ld_lds(&c.tail_done) >= L + 1; });
       // `red` may be overwritten; the outputs of both waves are in memory: hand over to the stages that read them
       st_lds(&c.red_free, L + 1);
       if (lane == 0) st_agent(p.flags + wg, epoch * 16 + (L + 1 < p.n_stages ? L + 1 : 15));
+      TS(7);
     }
   }
 }
@@ -1131,6 +1172,26 @@ __device__ __forceinline__ void ld_through8(const f32x4* const (&q)[8], f32x4 (&
       : "memory");
 }
 
+// The same with two more (the LoRA term tiles of a unit travel with its first eight partial tiles).
+__device__ __forceinline__ void ld_through10(const f32x4* const (&q)[10], f32x4 (&v)[10]) {
+  asm volatile(
+      "global_load_dwordx4 %0, %10, off sc0 sc1\n\t"
+      "global_load_dwordx4 %1, %11, off sc0 sc1\n\t"
+      "global_load_dwordx4 %2, %12, off sc0 sc1\n\t"
+      "global_load_dwordx4 %3, %13, off sc0 sc1\n\t"
+      "global_load_dwordx4 %4, %14, off sc0 sc1\n\t"
+      "global_load_dwordx4 %5, %15, off sc0 sc1\n\t"
+      "global_load_dwordx4 %6, %16, off sc0 sc1\n\t"
+      "global_load_dwordx4 %7, %17, off sc0 sc1\n\t"
+      "global_load_dwordx4 %8, %18, off sc0 sc1\n\t"
+      "global_load_dwordx4 %9, %19, off sc0 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7]), "=&v"(v[8]),
+        "=&v"(v[9])
+      : "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]), "v"(q[4]), "v"(q[5]), "v"(q[6]), "v"(q[7]), "v"(q[8]), "v"(q[9])
+      : "memory");
+}
+
 // units (tiles, or gate/up tile pairs) and groups of a level
 __device__ __host__ __forceinline__ int wide_units(const Stage& s) {
   if (s.pair) return s.N[0] >> 4;
@@ -1143,7 +1204,7 @@ __device__ __host__ __forceinline__ int wide_groups(const Stage& s, int NT) {
   return (wide_units(s) + upg - 1) / upg;
 }
 
-template <int MT>
+template <int MT, bool TRACE>
 __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
   constexpr int TPW = WCfg<MT>::TPW, D = WCfg<MT>::D, CKB = WCfg<MT>::CKB, NT = kSW * TPW;
   constexpr int kChunk = CKB * MT * 1024;                         // bytes of an input chunk: CKB k blocks, all rows
@@ -1168,7 +1229,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     c.x_done[tid] = 0;
     c.seg_arr[tid] = 0;
   }
-  if (tid < kMaxStages) { c.shr_next[tid] = 0; c.lvl_arr[tid] = 0; }
+  if (tid < kMaxStages) { c.shr_next[tid] = 0; c.lvl_arr[tid] = 0; c.exp_next[tid] = 0; }
   if (tid >= 64 && tid < 64 + kMaxRows) {
     const int m = tid - 64;
     int mask = 0, tenant = 0, r = 0;
@@ -1190,13 +1251,28 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
   __syncthreads();
   const int epoch = __builtin_amdgcn_readfirstlane(c.epoch);
 
+  // A wait that runs out is recorded in the status word and leaves the wave `dead`: it waits for nothing any more,
+  // draws no LoRA items and builds no lists (their inputs may not be there), and otherwise runs through its levels on
+  // whatever the buffers hold - every address it forms comes from the launch parameters, not from what it waited for.
+  // (No wave ends early here: an s_endpgm inside the item loops below made the compiler re-run an item for ever.)
+  // cond() is the same in every lane (an __all, or a word every lane reads): the loop is kept scalar.
+  bool dead = false;
   auto spin_until = [&](auto cond) __attribute__((always_inline)) {
     int spins = 0;
-    while (!cond()) {
-      if (++spins >= p.spin_limit) give_up(p.status);
+    while (!dead && !__builtin_amdgcn_readfirstlane((int)cond())) {
+      if (++spins >= p.spin_limit) {
+        if (lane == 0) st_agent(p.status, 1);
+        dead = true;
+      }
       __builtin_amdgcn_s_sleep(1);
     }
     compiler_fence();
+  };
+  auto barrier_wait = [&](int target) __attribute__((always_inline)) {
+    if (!dead && !grid_wait(p.flags, G, target, lane, p.spin_limit)) {
+      if (lane == 0) st_agent(p.status, 1);
+      dead = true;
+    }
   };
   auto wave_sync = [&]() __attribute__((always_inline)) {
     compiler_fence();
@@ -1210,13 +1286,96 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     const int NC = shrink_chunks(sg.K);
     const int items = ld_lds(&c.s_cnt) * NC;
     for (;;) {
+      // (The barrier keeps the compiler from fusing the one-lane store that ends an item with the one-lane ticket
+      // draw of the next: fused, lanes 1..63 went round the loop on their own, with ticket 0, for ever.)
+      __builtin_amdgcn_wave_barrier();
       int k = 0;
       if (lane == 0) k = __hip_atomic_fetch_add(&c.shr_next[L], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       k = __builtin_amdgcn_readfirstlane(k);
       const long it = (long)((wg + 97 * L) % G) + (long)k * G;
       if (it >= items) break;
       const int ms = c.s_rows[it / NC], m = ms & 0xff;
-      lora_shrink_item<MT>(p, sg, m, ms >> 8, c.r_ten[m], c.r_rank[m], (int)(it % NC), NC, epoch * 16 + L + 1, lane);
+      long long* ts = nullptr;
+      if (TRACE && k == 0) {  // the wave's first item of the level in detail: slots 8..12
+        ts = p.trace + (((size_t)wg * kMaxStages + L) * kWaves + w) * kTraceSlots + 9;
+        TS(8);
+      }
+      lora_shrink_item<MT, true, 16>(p, sg, m, ms >> 8, c.r_ten[m], c.r_rank[m], (int)(it % NC), NC, epoch * 16 + L + 1, lane, ts);
+    }
+  };
+  // The level's expand items: the LoRA term t W^B of one routed row at one site for a slab of 256 columns (four per
+  // lane), stored as fp32 tiles in the layout of the partial tiles, so that the sums below take it in like one more
+  // segment.  An item waits for the row's shrink partials (one flag per k chunk), adds them in chunk order, takes
+  // 32 ranks of W^B per round trip, stores, and publishes one word per (slab, row).  Drawn like the shrink items.
+  auto expand_items = [&](const int L, const Stage& sg) __attribute__((always_inline)) {
+    const int NC = shrink_chunks(sg.K);
+    const int N = sg.N[0];  // the sites of a level are equally wide
+    const int slabs = (N + 255) >> 8;
+    // (what is read from LDS below is the same in every lane; it is made scalar, so that the loops and waits of an
+    // item are plain scalar control flow)
+    const int items = __builtin_amdgcn_readfirstlane(ld_lds(&c.s_cnt)) * slabs;
+    const int lvl_tag = epoch * 16 + L + 1;
+    f32x4* const dtab = reinterpret_cast<f32x4*>(p.delta) + (size_t)((L & 1) ? p.delta_odd : 0) * (MT * 64);
+    int* const drd = p.dready + (size_t)(L & 1) * 3 * p.slabs_max * kMaxRows;
+    const int rmax = p.ad.r_max;
+    for (;;) {
+      __builtin_amdgcn_wave_barrier();  // (as in shrink_items)
+      int k = 0;
+      if (lane == 0) k = __hip_atomic_fetch_add(&c.exp_next[L], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      k = __builtin_amdgcn_readfirstlane(k);
+      const int it = (wg + 131 * L) % G + k * G;
+      if (it >= items) break;
+      const int e = it / slabs, j = it - e * slabs;
+      const int ms = __builtin_amdgcn_readfirstlane(c.s_rows[e]), m = ms & 0xff, sp = ms >> 8;
+      const int r = __builtin_amdgcn_readfirstlane(c.r_rank[m]), slot = shrink_slot(sg, m, sp);
+      const int tenant = __builtin_amdgcn_readfirstlane(c.r_ten[m]);
+      {  // the row's shrink partials are there: one flag per k chunk
+        const int* f = p.tpflag + slot * kTpStride + (lane < NC ? lane : 0);
+        spin_until([&]() { return __all(lane >= NC || ld_agent(f) == lvl_tag); });
+      }
+      const int n = j * 256 + 4 * lane;
+      const bool inb = n < N;
+      const size_t ldb = (size_t)N;
+      const gbf16* Bm = (const gbf16*)p.ad.B[tenant * MILORA_NUM_SITES + sg.site[sp]] + (inb ? n : 0);
+      const float* tp = p.tpart + (size_t)slot * p.nc_max * rmax;
+      const bool vec = ((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0;
+      float d[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int c0 = 0; c0 < r; c0 += 16) {
+        const int cu = c0 + (lane & 15);
+        // lane u (of every 16) sums rank c0 + u over the k chunks, in chunk order, 16 loads in flight per pass
+        float tl = 0.f;
+        for (int k0 = 0; k0 < NC; k0 += 16) {
+          float v[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u)
+            v[u] = ld_agent(tp + (size_t)(k0 + u < NC ? k0 + u : NC - 1) * rmax + (cu < r ? cu : 0));
+#pragma unroll
+          for (int u = 0; u < 16; ++u) tl += k0 + u < NC ? v[u] : 0.f;
+        }
+        if (vec) {
+          u32x2 bb[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(c0 + u < r ? c0 + u : r - 1) * ldb);
+#pragma unroll
+          for (int u = 0; u < 16; ++u) {
+            const float t = c0 + u < r ? __shfl(tl, u, 64) : 0.f;
+            d[0] += t * __uint_as_float(bb[u][0] << 16);
+            d[1] += t * __uint_as_float(bb[u][0] & 0xffff0000u);
+            d[2] += t * __uint_as_float(bb[u][1] << 16);
+            d[3] += t * __uint_as_float(bb[u][1] & 0xffff0000u);
+          }
+        } else {
+          for (int u = 0; u < 16 && c0 + u < r; ++u) {
+            const float t = __shfl(tl, u, 64);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)(c0 + u) * ldb + z]);
+          }
+        }
+      }
+      if (inb) st_through(dtab + ((size_t)(sp * (N >> 4) + (n >> 4)) * MT + (m >> 4)) * 64 + (m & 15) + 16 * ((n >> 2) & 3),
+                          f32x4{d[0], d[1], d[2], d[3]});
+      wait_all_mem();
+      st_agent(drd + (sp * p.slabs_max + j) * kMaxRows + m, lvl_tag);  // (by every lane, as the shrink flags)
     }
   };
 
@@ -1232,6 +1391,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     const long Wt = (long)groups * KT;
     const int act = Wt < (long)G ? (int)Wt : G;  // workgroups that get a piece of the level
     const int tag = epoch * 16 + L;
+    TS(0);
     // Segment tables of even and odd levels lie apart: a level that follows another without a barrier (o after q,k,v
     // when the caller supplies the attention output) must not touch what that one's sums still read.
     const int sbase = (L & 1) * p.wsegs;
@@ -1257,47 +1417,6 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
       }
       return u;
     };
-    // LoRA term of row m at site position sp for the four columns from ncol on; the row's shrink is published
-    auto lora_quad = [&](const int m, const int sp, const int ncol, float (&d)[4]) __attribute__((always_inline)) {
-      const int r = c.r_rank[m];
-      const size_t ldb = (size_t)sg.N[sp];
-      const gbf16* Bm = (const gbf16*)p.ad.B[c.r_ten[m] * MILORA_NUM_SITES + sg.site[sp]] + ncol;
-      const float* tf = p.tfin + (size_t)shrink_slot(sg, m, sp) * p.ad.r_max;
-      if (((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0) {
-        int cc = 0;
-        for (; cc + 16 <= r; cc += 16) {
-          u32x2 bb[16];
-          float t[16];
-#pragma unroll
-          for (int u = 0; u < 16; ++u) {
-            bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(cc + u) * ldb);
-            t[u] = ld_agent(tf + cc + u);
-          }
-#pragma unroll
-          for (int u = 0; u < 16; ++u) {
-            d[0] += t[u] * __uint_as_float(bb[u][0] << 16);
-            d[1] += t[u] * __uint_as_float(bb[u][0] & 0xffff0000u);
-            d[2] += t[u] * __uint_as_float(bb[u][1] << 16);
-            d[3] += t[u] * __uint_as_float(bb[u][1] & 0xffff0000u);
-          }
-        }
-        for (; cc < r; ++cc) {
-          const u32x2 bb = *reinterpret_cast<const gu32x2*>(Bm + (size_t)cc * ldb);
-          const float t = ld_agent(tf + cc);
-          d[0] += t * __uint_as_float(bb[0] << 16);
-          d[1] += t * __uint_as_float(bb[0] & 0xffff0000u);
-          d[2] += t * __uint_as_float(bb[1] << 16);
-          d[3] += t * __uint_as_float(bb[1] & 0xffff0000u);
-        }
-      } else {
-        for (int cc = 0; cc < r; ++cc) {
-          const float t = ld_agent(tf + cc);
-#pragma unroll
-          for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)cc * ldb + z]);
-        }
-      }
-    };
-
     if (w < kSW) {
       // ===================================== stream waves =====================================
       const int rd_off = sg.x_packed ? lane * 16 : ((lane & 15) * 4 + (lane >> 4)) * 16;
@@ -1355,6 +1474,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
               compiler_fence();
               st_lds(&c.x_done[w], xs + (chn < nch ? chn : nch));
               if (valid && seen <= xs + chn) spin_until([&]() { return (seen = ld_lds(&c.x_ready[0])) > xs + chn; });
+              if (TRACE && pos == lo && i == 0) TS(1);
             }
             const uint32_t mask = valid ? 0xffffffffu : 0u;
             const int chn = valid ? i / CKB : nch - 1;
@@ -1408,11 +1528,13 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
         ++segord;
         pos += len;
       }
+      TS(2);
     } else if (w == kLoader) {
       // ===================================== input loader =====================================
       if (sg.sync_before && L > 0) {
-        if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
+        barrier_wait(epoch * 16 + L);
       }
+      TS(1);
       const unsigned char* const Xb = reinterpret_cast<const unsigned char*>(sg.X);
       const bool xpk = sg.x_packed != 0;
       size_t loff[MT];
@@ -1454,22 +1576,21 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
       wait_vm<0>();
       lds_poke(ready_off, xs + issued);
       xs += issued;
-      if (p.lora) {  // the copies are out: help with the level's shrinks
-        spin_until([&]() { return ld_lds(&c.shr_ready) >= L + 1; });
-        shrink_items(L, sg);
-      }
+      TS(2);
+      if (p.lora) spin_until([&]() { return ld_lds(&c.shr_ready) >= L + 1; });  // the copies are out: help with the LoRA items
     } else {
       // ===================================== LoRA wave: the level's shrinks =====================================
       if (p.lora) {
         if (sg.sync_before && L > 0) {
-          if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
+          barrier_wait(epoch * 16 + L);
         }
+        TS(1);
         // the level's rows with a LoRA term, in row order (the same list in every workgroup); the loader wave may
         // still be drawing the previous level's items from the list when this level has no barrier before it
         if (L > 0) spin_until([&]() { return ld_lds(&c.lvl_arr[L - 1]) >= kWaves; });
-        if (lane == 0) c.s_cnt = 0;
+        if (lane == 0 && !dead) c.s_cnt = 0;
         wave_sync();
-        for (int s = 0; s < sg.n_seg; ++s)
+        for (int s = 0; s < sg.n_seg && !dead; ++s)
           for (int m0 = 0; m0 < p.M; m0 += 64) {
             const int m = m0 + lane;
             const bool has = m < p.M && ((c.r_mask[m < p.M ? m : 0] >> sg.site[s]) & 1);
@@ -1480,16 +1601,25 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
             if (lane == 0) c.s_cnt = base + __popcll(mask);
             wave_sync();
           }
-        if (lane == 0) st_lds(&c.shr_ready, L + 1);
-        shrink_items(L, sg);
+        if (lane == 0 && !dead) st_lds(&c.shr_ready, L + 1);
+        TS(2);
       }
+    }
+    if (w >= kSW && p.lora && !dead) {  // loader and LoRA wave: the level's shrinks, then the expands
+      shrink_items(L, sg);
+      TS(6);
+      expand_items(L, sg);
+      TS(3);
     }
     // ===================================== all waves: sum, LoRA term, glue, store =====================================
     {
-      // A wave's units share their 16 rows and lie in one group (two at most): a flag that has been seen stays, so
-      // the segment flags of a group and the shrink words of the rows at a site are polled once per wave.
-      int g_seen = -1, sp_seen = -1;
+      // A wave's units lie in one group (two at most): a flag that has been seen stays, so the segment flags of a
+      // group are polled once per wave.
+      int g_seen = -1;
       int uc = 0;
+      const f32x4* const dtab = reinterpret_cast<const f32x4*>(p.delta) + (size_t)((L & 1) ? p.delta_odd : 0) * (MT * 64);
+      const int* const drd = p.dready + (size_t)(L & 1) * 3 * p.slabs_max * kMaxRows;
+      TS(4);
       for (int ti = t0; ti < t1; ++ti)
         for (int mt = 0; mt < MT; ++mt, ++uc) {
           if ((uc & 7) != w) continue;
@@ -1508,24 +1638,23 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           const int wf = owner(x0), wl = owner(x0 + KT - 1), n = wl - wf + 1, sid0 = sbase + wf + g;
           const int m = mt * 16 + (lane & 15), q = lane >> 4;
           const int ncol = tile * 16 + q * 4;
-          // LoRA term of this lane's row and four columns at site position sp
-          auto lora_term = [&](const int sp, float (&d)[4]) __attribute__((always_inline)) {
-#pragma unroll
-            for (int z = 0; z < 4; ++z) d[z] = 0.f;
-            const bool has = p.lora && m < p.M && ((c.r_mask[m < p.M ? m : 0] >> sg.site[sp]) & 1);
-            if (sg.pair ? sp_seen != 3 : sp != sp_seen) {
-              const int* f = p.tready + shrink_slot(sg, m < p.M ? m : 0, sp);
-              spin_until([&]() { return __all(!has || ld_agent(f) == lvl_tag); });
-            }
-            if (has) lora_quad(m, sp, ncol, d);
-          };
-          float da[4], db[4];
-          lora_term(s, da);
-          if (sg.pair) lora_term(1, db);
-          sp_seen = sg.pair ? 3 : s;  // (a pair polls both of its sites in the first unit)
-          // the group's segments are there
-          if (g != g_seen) {
-            for (int b = 0; b < n; b += 64) {
+          // The LoRA terms of the unit's rows (stored by the expand items as tiles of this layout) and the group's
+          // segments are there: one poll loop over both kinds of flags.
+          const int mm = m < p.M ? m : 0;
+          const bool has_a = p.lora && m < p.M && ((c.r_mask[mm] >> sg.site[s]) & 1);
+          const bool has_b = sg.pair && p.lora && m < p.M && ((c.r_mask[mm] >> sg.site[1]) & 1);
+          const int* const fa = drd + (s * p.slabs_max + (tile >> 4)) * kMaxRows + mm;
+          const int* const fb = drd + (1 * p.slabs_max + (tile >> 4)) * kMaxRows + mm;
+          {
+            const int* const fs = p.segflag + sid0 + (lane < n ? lane : 0);
+            const bool poll_seg = g != g_seen;
+            spin_until([&]() {
+              bool ok = !has_a || ld_agent(fa) == lvl_tag;
+              ok = ok && (!has_b || ld_agent(fb) == lvl_tag);
+              ok = ok && (!poll_seg || lane >= n || ld_agent(fs) == tag);
+              return __all(ok);
+            });
+            for (int b = 64; poll_seg && b < n; b += 64) {  // (more than 64 segments per group: tiny levels on a large grid)
               const int i = b + lane;
               const int* f = p.segflag + sid0 + (i < n ? i : 0);
               spin_until([&]() { return __all(i >= n || ld_agent(f) == tag); });
@@ -1542,6 +1671,8 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           }
           const size_t sstride = (size_t)NT * MT * 64;
           const f32x4* const P0 = reinterpret_cast<const f32x4*>(p.wpart) + ((size_t)sid0 * NT + a0) * (MT * 64) + mt * 64 + lane;
+          const f32x4* const Da = dtab + ((size_t)(s * (sg.N[0] >> 4) + tile) * MT + mt) * 64 + lane;
+          const f32x4* const Db = dtab + ((size_t)((sg.N[0] >> 4) + tile) * MT + mt) * 64 + lane;
           // bias and residual travel with the partial tiles
           u32x2 g_bias = {0u, 0u}, g_rb = {0u, 0u};
           f32x4 g_rf = {0.f, 0.f, 0.f, 0.f};
@@ -1550,17 +1681,32 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
             if (sg.resid_bf16) g_rb = *reinterpret_cast<const u32x2*>(sg.resid_bf16 + (size_t)m * sg.ld_resid + ncol);
             if (sg.resid_f32) g_rf = *reinterpret_cast<const f32x4*>(sg.resid_f32 + (size_t)m * sg.ld_resid + ncol);
           }
-          if (sg.pair) {  // gate and up tiles of four segments per round trip
+          f32x4 da = {0.f, 0.f, 0.f, 0.f}, db = {0.f, 0.f, 0.f, 0.f};
+          if (sg.pair) {  // gate and up tiles of four segments per round trip, the LoRA term tiles with the first
             for (int i = 0; i < n; i += 4) {
-              const f32x4* q8[8];
-              f32x4 v[8];
+              const f32x4* q10[10];
+              f32x4 v[10];
 #pragma unroll
               for (int u = 0; u < 4; ++u) {
                 const int iu = i + u < n ? i + u : n - 1;
-                q8[u] = P0 + iu * sstride;
-                q8[4 + u] = P0 + iu * sstride + MT * 64;
+                q10[u] = P0 + iu * sstride;
+                q10[4 + u] = P0 + iu * sstride + MT * 64;
               }
-              ld_through8(q8, v);
+              q10[8] = has_a ? Da : P0;
+              q10[9] = has_b ? Db : P0;
+              if (i == 0) {
+                ld_through10(q10, v);
+                if (has_a) da = v[8];
+                if (has_b) db = v[9];
+              } else {
+                const f32x4* q8[8];
+                f32x4 v8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) q8[u] = q10[u];
+                ld_through8(q8, v8);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = v8[u];
+              }
 #pragma unroll
               for (int u = 0; u < 4; ++u)
                 if (i + u < n) {
@@ -1570,11 +1716,24 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
             }
           } else {  // eight segments per round trip
             for (int i = 0; i < n; i += 8) {
-              const f32x4* q8[8];
-              f32x4 v[8];
+              const f32x4* q10[10];
+              f32x4 v[10];
 #pragma unroll
-              for (int u = 0; u < 8; ++u) q8[u] = P0 + (i + u < n ? i + u : n - 1) * sstride;
-              ld_through8(q8, v);
+              for (int u = 0; u < 8; ++u) q10[u] = P0 + (i + u < n ? i + u : n - 1) * sstride;
+              q10[8] = has_a ? Da : P0;
+              q10[9] = P0;
+              if (i == 0) {
+                ld_through10(q10, v);
+                if (has_a) da = v[8];
+              } else {
+                const f32x4* q8[8];
+                f32x4 v8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) q8[u] = q10[u];
+                ld_through8(q8, v8);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = v8[u];
+              }
 #pragma unroll
               for (int u = 0; u < 8; ++u)
                 if (i + u < n) sa += v[u];
@@ -1617,6 +1776,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     }
     // ---- level end: the last wave to get here hands the level over ----
     wait_all_mem();
+    TS(5);
     {
       int old = 0;
       if (lane == 0) old = __hip_atomic_fetch_add(&c.lvl_arr[L], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1638,10 +1798,13 @@ int stream_grid() {
   int dev = 0, cus = 0, occ = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_stream_kernel<MT>),
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_stream_kernel<MT, false>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
     return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_stream_kernel<MT>, kThreads, kLdsBytes) != hipSuccess)
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_stream_kernel<MT, true>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+    return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_stream_kernel<MT, false>, kThreads, kLdsBytes) != hipSuccess)
     return 0;
   if (occ < 1 || cus < 1) return 0;
   cached = cus > kMaxGrid ? kMaxGrid : cus;
@@ -1657,13 +1820,19 @@ int grid_for(int MT) {
   }
 }
 
-int launch_stream(const Params& p, int MT, int G, hipStream_t st) {
+template <bool TRACE>
+void launch_stream_t(const Params& p, int MT, int G, hipStream_t st) {
   switch (MT) {
-    case 1: hipLaunchKernelGGL(decode_stream_kernel<1>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
-    case 2: hipLaunchKernelGGL(decode_stream_kernel<2>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
-    case 4: hipLaunchKernelGGL(decode_stream_kernel<4>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
-    default: hipLaunchKernelGGL(decode_stream_kernel<8>, dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
+    case 1: hipLaunchKernelGGL((decode_stream_kernel<1, TRACE>), dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
+    case 2: hipLaunchKernelGGL((decode_stream_kernel<2, TRACE>), dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
+    case 4: hipLaunchKernelGGL((decode_stream_kernel<4, TRACE>), dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
+    default: hipLaunchKernelGGL((decode_stream_kernel<8, TRACE>), dim3(G), dim3(kThreads), kLdsBytes, st, p); break;
   }
+}
+
+int launch_stream(const Params& p, int MT, int G, hipStream_t st) {
+  if (p.trace) launch_stream_t<true>(p, MT, G, st);
+  else launch_stream_t<false>(p, MT, G, st);
   return check_launch();
 }
 
@@ -1675,10 +1844,13 @@ int wide_grid() {
   int dev = 0, cus = 0, occ = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_wide_kernel<MT>), hipFuncAttributeMaxDynamicSharedMemorySize,
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_wide_kernel<MT, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
                           kLdsBytes) != hipSuccess)
     return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_wide_kernel<MT>, kThreads, kLdsBytes) != hipSuccess) return 0;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_wide_kernel<MT, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kLdsBytes) != hipSuccess)
+    return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_wide_kernel<MT, false>, kThreads, kLdsBytes) != hipSuccess) return 0;
   if (occ < 1 || cus < 1) return 0;
   cached = cus > kWideGridMax ? kWideGridMax : cus;
   return cached;
@@ -1764,6 +1936,10 @@ struct DecodeWs {
   int* segflag;    // wide kernel, layer decode of more than 32 rows only: see Params
   float* wss;
   float* wpart;
+  int* tpflag;
+  int* dready;
+  float* delta;
+  int delta_odd, slabs_max;
   size_t bytes;
 };
 
@@ -1780,17 +1956,25 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max, bool wide =
   const size_t o_v = take((size_t)rows * d * sizeof(bf16_t));
   const size_t o_hb = take((size_t)rows * d * sizeof(bf16_t));
   const size_t o_m = take((size_t)rows * F * sizeof(bf16_t));
-  size_t o_sf = 0, o_ss = 0, o_wp = 0;
+  size_t o_sf = 0, o_ss = 0, o_wp = 0, o_tp = 0, o_dr = 0, o_dt = 0;
+  // LoRA term tiles of the wide kernel: the sites of an even level (q,k,v or gate,up) side by side, then those of an
+  // odd level (o or down); 256-column slabs of the widest site
+  const int tiles_even = 3 * (d >> 4) > 2 * (F >> 4) ? 3 * (d >> 4) : 2 * (F >> 4), tiles_odd = d >> 4;
+  const int slabs_max = (big + 255) >> 8;
   if (wide) {
     const int MT = mt_for(M), segs = 2 * wide_segments(MT, d, F);
     o_sf = take((size_t)segs * sizeof(int));
     o_ss = take((size_t)segs * rows * sizeof(float));
     o_wp = take((size_t)segs * wide_tiles_per_group(MT) * MT * 1024);
+    o_tp = take((size_t)kSlotsPerRow * kMaxRows * kTpStride * sizeof(int));
+    o_dr = take((size_t)2 * 3 * slabs_max * kMaxRows * sizeof(int));
+    o_dt = take((size_t)(tiles_even + tiles_odd) * MT * 1024);
   }
   char* b = (char*)base;
   int* fl = (int*)(b + o_fl);
   return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (int*)(b + o_p) + kSlotsPerRow * kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
-                  (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb), (bf16_t*)(b + o_m), (int*)(b + o_sf), (float*)(b + o_ss), (float*)(b + o_wp), off};
+                  (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb), (bf16_t*)(b + o_m), (int*)(b + o_sf), (float*)(b + o_ss), (float*)(b + o_wp),
+                  (int*)(b + o_tp), (int*)(b + o_dr), (float*)(b + o_dt), tiles_even, slabs_max, off};
 }
 
 void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const AdapterView& ad, const int32_t* tenant_id,
@@ -1799,7 +1983,9 @@ void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const
   p.lora = 1;
   p.tpart = ws.tpart; p.tfin = ws.tfin; p.tcount = ws.tcount; p.tready = ws.tready; p.nc_max = shrink_chunks(Kmax);
   p.flags = ws.flags; p.status = ws.status; p.spin_limit = g_wait_limit.load(std::memory_order_relaxed);
+  p.trace = nullptr;
   p.wpart = ws.wpart; p.wss = ws.wss; p.segflag = ws.segflag; p.wsegs = 0;
+  p.tpflag = ws.tpflag; p.dready = ws.dready; p.delta = ws.delta; p.delta_odd = ws.delta_odd; p.slabs_max = ws.slabs_max;
 }
 
 }  // namespace
@@ -1881,15 +2067,19 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     l.tpos0 = 3;
     units[3] = d >> 4;
   }
+  if (marks && marks->trace) p.trace = marks->trace;
   if (wide) {
     for (int L = 0; L < 4; ++L) {
       p.st[L] = lv[L];
       p.st[L].lora_shrink = 1;
     }
     p.n_stages = 4;
+    if (marks) { marks->grid = G; marks->stages = 4; }
     p.wsegs = wide_segments(MT, d, F);
-    if (MT == 4) hipLaunchKernelGGL(decode_wide_kernel<4>, dim3(G), dim3(kThreads), kLdsBytes, st, p);
-    else hipLaunchKernelGGL(decode_wide_kernel<8>, dim3(G), dim3(kThreads), kLdsBytes, st, p);
+    if (MT == 4 && !p.trace) hipLaunchKernelGGL((decode_wide_kernel<4, false>), dim3(G), dim3(kThreads), kLdsBytes, st, p);
+    else if (MT == 4) hipLaunchKernelGGL((decode_wide_kernel<4, true>), dim3(G), dim3(kThreads), kLdsBytes, st, p);
+    else if (!p.trace) hipLaunchKernelGGL((decode_wide_kernel<8, false>), dim3(G), dim3(kThreads), kLdsBytes, st, p);
+    else hipLaunchKernelGGL((decode_wide_kernel<8, true>), dim3(G), dim3(kThreads), kLdsBytes, st, p);
     const int rcw = check_launch();
     if (rcw) return rcw;
     if (marks && marks->n > 0) (void)hipEventRecord(marks->ev[0], st);
@@ -1897,10 +2087,17 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
   }
   for (int L = 0; L < 4; ++L)
     if (!push_level(p, lv[L], units[L], G, nsm)) return MILORA_ERANGE;
+  if (marks) { marks->grid = G; marks->stages = p.n_stages; }
   int rc = launch_stream(p, MT, G, st);
   if (rc) return rc;
   if (marks && marks->n > 0) (void)hipEventRecord(marks->ev[0], st);
   return MILORA_OK;
+}
+
+size_t decode_trace_bytes() { return (size_t)kMaxGrid * kMaxStages * kWaves * kTraceSlots * sizeof(long long); }
+int decode_trace_dims(int* stages_max, int* waves, int* slots) {
+  *stages_max = kMaxStages; *waves = kWaves; *slots = kTraceSlots;
+  return kMaxGrid;
 }
 
 // ---- layer decode on scratch memory the library itself holds ----------------------------------------------------

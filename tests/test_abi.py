@@ -43,13 +43,16 @@ def test_workspace_sizes_are_monotone_and_reject_bad_sizes():
     assert 0 < a < b
     # above 32 rows the workspace also holds the wide-batch kernel's tables: two halves of (256 workgroups + column
     # groups of the widest level) segments, each 96 tiles of 1 KiB partial sums (24 tiles x 4 row tiles up to 64
-    # rows, 12 x 8 above), a flag and the rows' sums of squares; 11008 / 16 gate/up pairs in groups of 12 or 6
+    # rows, 12 x 8 above), a flag and the rows' sums of squares; 11008 / 16 gate/up pairs in groups of 12 or 6;
+    # and the LoRA term tiles (1 KiB per tile and row tile: 2 * 688 gate/up tiles + 256 of o or down) with their flags
     c = mb.layer_decode_workspace_bytes(33, 4096, 11008, 32)
     segs = 2 * (256 + 58)
-    assert segs * (96 * 1024 + 64 * 4 + 4) <= c <= segs * (96 * 1024 + 64 * 4 + 4) + (1 << 23)
+    lora_tiles = (2 * 688 + 256) * 4 * 1024
+    assert segs * (96 * 1024 + 64 * 4 + 4) + lora_tiles <= c <= segs * (96 * 1024 + 64 * 4 + 4) + lora_tiles + (1 << 23)
     c = mb.layer_decode_workspace_bytes(65, 4096, 11008, 32)
     segs = 2 * (256 + 115)
-    assert segs * (96 * 1024 + 128 * 4 + 4) <= c <= segs * (96 * 1024 + 128 * 4 + 4) + (1 << 23)
+    lora_tiles = (2 * 688 + 256) * 8 * 1024
+    assert segs * (96 * 1024 + 128 * 4 + 4) + lora_tiles <= c <= segs * (96 * 1024 + 128 * 4 + 4) + lora_tiles + (1 << 23)
     assert mb.layer_decode_workspace_bytes(128, 4096, 11008, 32) >= c
     assert mb.layer_decode_workspace_bytes(129, 4096, 11008, 32) == 0  # beyond the decode batch limit
     assert mb.routed_linear_workspace_bytes(32768, 4096, 4096, 32) >= 32768 * 32 * 4
