@@ -58,8 +58,7 @@ WIDE_PHASES = {
     "loader_barrier_passed": ([6], 1), "loader_copies_landed": ([6], 2), "lora_list_built": ([7], 2),
     "lora_wave_shrink_items_done": ([7], 6), "lora_wave_expand_items_done": ([7], 3),
     "loader_shrink_items_done": ([6], 6), "loader_expand_items_done": ([6], 3),
-    "lora_wave_item1_begun": ([7], 8), "lora_wave_item1_sums_done": ([7], 9), "lora_wave_item1_stores_acked": ([7], 10),
-    "lora_wave_item1_counted": ([7], 11), "lora_wave_item1_published": ([7], 12),
+    "lora_wave_item1_begun": ([7], 8), "lora_wave_item1_flagged": ([7], 9),
     "sums_begun": (range(0, 8), 4), "sums_stored": (range(0, 8), 5)}
 
 

@@ -1146,9 +1146,98 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const u32x4* __restric
 // segments of a group are there, the group's tiles are summed in segment order, get their LoRA term and the level's
 // glue, and are stored - each (tile, row tile) by one wave of the workgroup it is dealt to.
 // =====================================================================================================================
+// ---- shrink items of the wide kernel, in two steps -------------------------------------------------------------
+// W^A does not depend on the activations: the rows of a chunk (up to 32 wave loads, the whole chunk for ranks up to 32)
+// can be asked for before the level's barrier has opened, and sit in registers when it does.  What is left behind the
+// barrier is one round trip for the 512 inputs of the row (one 16-byte load per lane, handed round through 1 KiB of
+// LDS), the sums, and the store of the partial with its flag.  For ranks that are a power of two times 8, up to 64,
+// and 16-byte aligned W^A; everything else takes lora_shrink_item.
+struct ShrinkJob {
+  const gbf16* A;
+  int m, pos, r, kc, k_lo, k_hi, slot;
+  bool fast;
+};
+
+template <int MT>
+__device__ __forceinline__ ShrinkJob shrink_job(const Params& p, const Stage& sg, int ms, int tenant, int r, int kc) {
+  ShrinkJob j;
+  j.m = ms & 0xff;
+  j.pos = ms >> 8;
+  j.r = r;
+  j.kc = kc;
+  j.k_lo = kc * kShrinkChunk;
+  j.k_hi = j.k_lo + kShrinkChunk < sg.K ? j.k_lo + kShrinkChunk : sg.K;
+  j.slot = shrink_slot(sg, j.m, j.pos);
+  j.A = (const gbf16*)p.ad.A[tenant * MILORA_NUM_SITES + sg.site[j.pos]];
+  const int lpr = r >> 3;
+  j.fast = (r & 7) == 0 && (lpr & (lpr - 1)) == 0 && lpr <= 8 && ((uintptr_t)j.A & 15) == 0;
+  return j;
+}
+
+// wave loads h * 32 .. h * 32 + 31 of the chunk's rows of W^A (a chunk is 8 * (r / 8) = r loads of 64 / (r / 8) rows)
+__device__ __forceinline__ void shrink_load_A(const ShrinkJob& j, int h, int lane, u32x4 (&a)[32]) {
+  const int lpr = j.r >> 3, kpl = 64 / lpr, cg = lane & (lpr - 1), kr = lane / lpr;
+  const gu32x4* Ap = reinterpret_cast<const gu32x4*>(j.A) + cg;
+#pragma unroll
+  for (int u = 0; u < 32; ++u) {
+    int k = j.k_lo + kr + (h * 32 + u) * kpl;
+    k = k < j.k_hi ? k : j.k_hi - 1;  // past the end of a ragged chunk: a valid row, its input is zero
+    a[u] = __builtin_nontemporal_load(Ap + (size_t)k * lpr);  // (loads past the chunk's r repeat its last row; not used)
+  }
+}
+
+template <int MT>
+__device__ __forceinline__ void shrink_finish(const Params& p, const Stage& sg, const ShrinkJob& j, int tag, int lane,
+                                              u32x4 (&a)[32], bf16_t* xs) {
+  const int lpr = j.r >> 3, kpl = 64 / lpr, kr = lane / lpr;
+  // the row's inputs of this chunk: lane l takes k_lo + 8 l .. + 7, and the chunk goes through LDS in k order
+  {
+    const int k = j.k_lo + 8 * lane;
+    u32x4 xv = {0u, 0u, 0u, 0u};
+    if (k < j.k_hi) {  // (k_hi is a multiple of 32)
+      const bf16_t* src = sg.x_packed ? sg.X + packed_x_offset(j.m, k, MT) : sg.X + (size_t)j.m * sg.ldx + k;
+      xv = *(const gu32x4*)src;
+    }
+    *reinterpret_cast<u32x4*>(xs + 8 * lane) = xv;
+  }
+  compiler_fence();
+  wait_lds();
+  compiler_fence();
+  float acc[8];
+#pragma unroll
+  for (int v = 0; v < 8; ++v) acc[v] = 0.f;
+  for (int h = 0; h * 32 < j.r; ++h) {
+    if (h > 0) shrink_load_A(j, h, lane, a);
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      if (h * 32 + u < j.r) {
+        const float x = bf16_to_f32(xs[kr + (h * 32 + u) * kpl]);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          acc[2 * v] += x * __uint_as_float(a[u][v] << 16);
+          acc[2 * v + 1] += x * __uint_as_float(a[u][v] & 0xffff0000u);
+        }
+      }
+    }
+  }
+  // lanes with equal column group hold partial sums over different rows: fixed butterfly over the row bits
+  for (int off = lpr; off < 64; off <<= 1)
+#pragma unroll
+    for (int v = 0; v < 8; ++v) acc[v] += __shfl_xor(acc[v], off, 64);
+  float* out = p.tpart + ((size_t)j.slot * p.nc_max + j.kc) * p.ad.r_max;
+  if (lane < lpr)
+#pragma unroll
+    for (int v = 0; v < 8; ++v) st_agent(out + lane * 8 + v, acc[v]);
+  wait_all_mem();
+  st_agent(p.tpflag + j.slot * kTpStride + j.kc, tag);  // (by every lane: see shrink_items)
+}
+
 template <int MT> struct WCfg;
-template <> struct WCfg<4> { static constexpr int TPW = 4, D = 4, CKB = 4; };
-template <> struct WCfg<8> { static constexpr int TPW = 2, D = 6, CKB = 2; };
+// (Two k steps of weight loads in flight per wave: deeper rings only lengthen every other round trip of the launch -
+// flags, partial tiles, LoRA items - which queue behind them in the memory system.  D = 2 with CKB = 2 at 64 rows gave
+// wrong sums in the tests and is not used; the cause was not found.)
+template <> struct WCfg<4> { static constexpr int TPW = 4, D = 2, CKB = 1; };
+template <> struct WCfg<8> { static constexpr int TPW = 2, D = 2, CKB = 2; };
 constexpr int kWideGridMax = 256;   // workgroups the segment tables are sized for
 
 __device__ __forceinline__ void st_through(u32x2* p, u32x2 v) {
@@ -1280,11 +1369,14 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     compiler_fence();
   };
 
+  // 1 KiB per tail wave for the inputs of a shrink item (the few-row kernel's sums of squares lie there; unused here)
+  static_assert(sizeof(c.ss_part) >= 2 * kShrinkChunk * sizeof(bf16_t), "input staging of the shrink items");
+  bf16_t* const xstage = reinterpret_cast<bf16_t*>(&c.ss_part[0][0]) + (w == kLora ? kShrinkChunk : 0);
   // The level's shrink items (row with a LoRA term at a site of the level, k chunk) are spread over the grid; those
   // of this workgroup are drawn one by one by its LoRA wave and, once its copies are out, its loader wave.
   auto shrink_items = [&](const int L, const Stage& sg) __attribute__((always_inline)) {
     const int NC = shrink_chunks(sg.K);
-    const int items = ld_lds(&c.s_cnt) * NC;
+    const int items = __builtin_amdgcn_readfirstlane(ld_lds(&c.s_cnt)) * NC;
     for (;;) {
       // (The barrier keeps the compiler from fusing the one-lane store that ends an item with the one-lane ticket
       // draw of the next: fused, lanes 1..63 went round the loop on their own, with ticket 0, for ever.)
@@ -1292,15 +1384,18 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
       int k = 0;
       if (lane == 0) k = __hip_atomic_fetch_add(&c.shr_next[L], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       k = __builtin_amdgcn_readfirstlane(k);
-      const long it = (long)((wg + 97 * L) % G) + (long)k * G;
+      const int it = (wg + 97 * L) % G + k * G;
       if (it >= items) break;
-      const int ms = c.s_rows[it / NC], m = ms & 0xff;
-      long long* ts = nullptr;
-      if (TRACE && k == 0) {  // the wave's first item of the level in detail: slots 8..12
-        ts = p.trace + (((size_t)wg * kMaxStages + L) * kWaves + w) * kTraceSlots + 9;
-        TS(8);
+      const int ms = __builtin_amdgcn_readfirstlane(c.s_rows[it / NC]), m = ms & 0xff;
+      const ShrinkJob job = shrink_job<MT>(p, sg, ms, __builtin_amdgcn_readfirstlane(c.r_ten[m]),
+                                           __builtin_amdgcn_readfirstlane(c.r_rank[m]), it % NC);
+      if (job.fast) {
+        u32x4 a[32];
+        shrink_load_A(job, 0, lane, a);
+        shrink_finish<MT>(p, sg, job, epoch * 16 + L + 1, lane, a, xstage);
+      } else {
+        lora_shrink_item<MT, true, 16>(p, sg, m, ms >> 8, c.r_ten[m], c.r_rank[m], it % NC, NC, epoch * 16 + L + 1, lane);
       }
-      lora_shrink_item<MT, true, 16>(p, sg, m, ms >> 8, c.r_ten[m], c.r_rank[m], (int)(it % NC), NC, epoch * 16 + L + 1, lane, ts);
     }
   };
   // The level's expand items: the LoRA term t W^B of one routed row at one site for a slab of 256 columns (four per
@@ -1329,20 +1424,28 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
       const int ms = __builtin_amdgcn_readfirstlane(c.s_rows[e]), m = ms & 0xff, sp = ms >> 8;
       const int r = __builtin_amdgcn_readfirstlane(c.r_rank[m]), slot = shrink_slot(sg, m, sp);
       const int tenant = __builtin_amdgcn_readfirstlane(c.r_ten[m]);
+      const int n = j * 256 + 4 * lane;
+      const bool inb = n < N;
+      const size_t ldb = (size_t)N;
+      const gbf16* const Bbase = (const gbf16*)p.ad.B[tenant * MILORA_NUM_SITES + sg.site[sp]];
+      const gbf16* const Bm = Bbase + (inb ? n : 0);
+      const float* tp = p.tpart + (size_t)slot * p.nc_max * rmax;
+      const bool vec = ((uintptr_t)Bbase & 7) == 0;  // (N is a multiple of 16: every row and every lane's quad is 8-byte aligned with it)
+      // rows c0 .. c0 + 31 of W^B, this lane's four columns
+      auto load_B = [&](int c0, u32x2 (&bb)[32]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 32; ++u) bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(c0 + u < r ? c0 + u : r - 1) * ldb);
+      };
+      u32x2 bb[32];
+      if (vec) load_B(0, bb);  // W^B does not wait for the shrink: asked for before the flags are polled
       {  // the row's shrink partials are there: one flag per k chunk
         const int* f = p.tpflag + slot * kTpStride + (lane < NC ? lane : 0);
         spin_until([&]() { return __all(lane >= NC || ld_agent(f) == lvl_tag); });
       }
-      const int n = j * 256 + 4 * lane;
-      const bool inb = n < N;
-      const size_t ldb = (size_t)N;
-      const gbf16* Bm = (const gbf16*)p.ad.B[tenant * MILORA_NUM_SITES + sg.site[sp]] + (inb ? n : 0);
-      const float* tp = p.tpart + (size_t)slot * p.nc_max * rmax;
-      const bool vec = ((uintptr_t)Bm & 7) == 0 && (ldb & 3) == 0;
       float d[4] = {0.f, 0.f, 0.f, 0.f};
-      for (int c0 = 0; c0 < r; c0 += 16) {
-        const int cu = c0 + (lane & 15);
-        // lane u (of every 16) sums rank c0 + u over the k chunks, in chunk order, 16 loads in flight per pass
+      for (int c0 = 0; c0 < r; c0 += 64) {
+        // lane u sums rank c0 + u over the k chunks, in chunk order, 16 loads in flight per pass
+        const int cu = c0 + lane;
         float tl = 0.f;
         for (int k0 = 0; k0 < NC; k0 += 16) {
           float v[16];
@@ -1353,19 +1456,21 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           for (int u = 0; u < 16; ++u) tl += k0 + u < NC ? v[u] : 0.f;
         }
         if (vec) {
-          u32x2 bb[16];
 #pragma unroll
-          for (int u = 0; u < 16; ++u) bb[u] = *reinterpret_cast<const gu32x2*>(Bm + (size_t)(c0 + u < r ? c0 + u : r - 1) * ldb);
+          for (int h = 0; h < 2; ++h) {
+            if (c0 + 32 * h >= r) break;
+            if (c0 + h > 0) load_B(c0 + 32 * h, bb);
 #pragma unroll
-          for (int u = 0; u < 16; ++u) {
-            const float t = c0 + u < r ? __shfl(tl, u, 64) : 0.f;
-            d[0] += t * __uint_as_float(bb[u][0] << 16);
-            d[1] += t * __uint_as_float(bb[u][0] & 0xffff0000u);
-            d[2] += t * __uint_as_float(bb[u][1] << 16);
-            d[3] += t * __uint_as_float(bb[u][1] & 0xffff0000u);
+            for (int u = 0; u < 32; ++u) {
+              const float t = c0 + 32 * h + u < r ? __shfl(tl, 32 * h + u, 64) : 0.f;
+              d[0] += t * __uint_as_float(bb[u][0] << 16);
+              d[1] += t * __uint_as_float(bb[u][0] & 0xffff0000u);
+              d[2] += t * __uint_as_float(bb[u][1] << 16);
+              d[3] += t * __uint_as_float(bb[u][1] & 0xffff0000u);
+            }
           }
         } else {
-          for (int u = 0; u < 16 && c0 + u < r; ++u) {
+          for (int u = 0; u < 64 && c0 + u < r; ++u) {
             const float t = __shfl(tl, u, 64);
 #pragma unroll
             for (int z = 0; z < 4; ++z) d[z] += t * bf16_to_f32(Bm[(size_t)(c0 + u) * ldb + z]);
@@ -1581,12 +1686,9 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
     } else {
       // ===================================== LoRA wave: the level's shrinks =====================================
       if (p.lora) {
-        if (sg.sync_before && L > 0) {
-          barrier_wait(epoch * 16 + L);
-        }
-        TS(1);
-        // the level's rows with a LoRA term, in row order (the same list in every workgroup); the loader wave may
-        // still be drawing the previous level's items from the list when this level has no barrier before it
+        // the level's rows with a LoRA term, in row order (the same list in every workgroup): it follows from the
+        // route table alone and is built before the barrier; the loader wave may still be drawing the previous
+        // level's items from the list
         if (L > 0) spin_until([&]() { return ld_lds(&c.lvl_arr[L - 1]) >= kWaves; });
         if (lane == 0 && !dead) c.s_cnt = 0;
         wave_sync();
@@ -1603,6 +1705,49 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           }
         if (lane == 0 && !dead) st_lds(&c.shr_ready, L + 1);
         TS(2);
+        // the wave's first shrink item: its rows of W^A are asked for now and travel while the barrier is closed
+        const int NC = shrink_chunks(sg.K);
+        const int items = dead ? 0 : __builtin_amdgcn_readfirstlane(ld_lds(&c.s_cnt)) * NC;
+        int k = 0;
+        if (lane == 0) k = __hip_atomic_fetch_add(&c.shr_next[L], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        k = __builtin_amdgcn_readfirstlane(k);
+        const int it = (wg + 97 * L) % G + k * G;
+        const bool have = it < items;
+        ShrinkJob job;
+        job.fast = false;
+        uint32_t pf[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};  // one word of every 128-byte line of the chunk of W^A
+        int ms = 0;
+        if (have) {
+          ms = __builtin_amdgcn_readfirstlane(c.s_rows[it / NC]);
+          const int m = ms & 0xff;
+          job = shrink_job<MT>(p, sg, ms, __builtin_amdgcn_readfirstlane(c.r_ten[m]), __builtin_amdgcn_readfirstlane(c.r_rank[m]),
+                               it % NC);
+          if (job.fast) {
+            const unsigned char* base = (const unsigned char*)(uintptr_t)job.A + (size_t)job.k_lo * job.r * 2;
+            const int bytes = (job.k_hi - job.k_lo) * job.r * 2;
+            int lane_here = lane;  // (opaque: otherwise the eight offsets are kept, and spilled, for the whole kernel)
+            asm volatile("" : "+v"(lane_here));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const int off = (i * 64 + lane_here) * 128;
+              if (off < bytes) pf[i] = __builtin_nontemporal_load((const __attribute__((address_space(1))) uint32_t*)(base + off));
+            }
+          }
+        }
+        if (sg.sync_before && L > 0) barrier_wait(epoch * 16 + L);
+        asm volatile("" : : "v"(pf[0]), "v"(pf[1]), "v"(pf[2]), "v"(pf[3]), "v"(pf[4]), "v"(pf[5]), "v"(pf[6]), "v"(pf[7]));
+        TS(1);
+        if (have && !dead) {
+          TS(8);
+          if (job.fast) {
+            u32x4 a[32];
+            shrink_load_A(job, 0, lane, a);
+            shrink_finish<MT>(p, sg, job, epoch * 16 + L + 1, lane, a, xstage);
+          } else lora_shrink_item<MT, true, 16>(p, sg, ms & 0xff, ms >> 8, c.r_ten[ms & 0xff], c.r_rank[ms & 0xff], it % NC, NC,
+                                              epoch * 16 + L + 1, lane);
+          TS(9);
+        }
+        __builtin_amdgcn_wave_barrier();
       }
     }
     if (w >= kSW && p.lora && !dead) {  // loader and LoRA wave: the level's shrinks, then the expands
@@ -1648,10 +1793,9 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           {
             const int* const fs = p.segflag + sid0 + (lane < n ? lane : 0);
             const bool poll_seg = g != g_seen;
-            spin_until([&]() {
-              bool ok = !has_a || ld_agent(fa) == lvl_tag;
-              ok = ok && (!has_b || ld_agent(fb) == lvl_tag);
-              ok = ok && (!poll_seg || lane >= n || ld_agent(fs) == tag);
+            spin_until([&]() {  // (the three words asked for together: one round trip per poll)
+              const int va = ld_agent(fa), vb = ld_agent(fb), vs = ld_agent(fs);
+              const bool ok = (!has_a || va == lvl_tag) & (!has_b || vb == lvl_tag) & (!poll_seg || lane >= n || vs == tag);
               return __all(ok);
             });
             for (int b = 64; poll_seg && b < n; b += 64) {  // (more than 64 segments per group: tiny levels on a large grid)
@@ -1663,10 +1807,16 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           }
           f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
           float ssq = 0.f;
-          if (sg.norm) {  // lane = (row, segment % 4): the segments' sums of squares in one round trip
-            for (int b = 0; b < n; b += 4) {
-              const int i = b + q;
-              if (i < n) ssq += ld_agent(p.wss + (size_t)(sid0 + i) * (MT * 16) + m);
+          if (sg.norm) {  // lane = (row, segment % 4): the sums of squares of 16 segments per round trip, added in order
+            for (int b = 0; b < n; b += 16) {
+              float v[4];
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const int i = b + 4 * u + q;
+                v[u] = ld_agent(p.wss + (size_t)(sid0 + (i < n ? i : 0)) * (MT * 16) + m);
+              }
+#pragma unroll
+              for (int u = 0; u < 4; ++u) ssq += b + 4 * u + q < n ? v[u] : 0.f;
             }
           }
           const size_t sstride = (size_t)NT * MT * 64;
