@@ -127,7 +127,10 @@ int milora_last_hip_error(void);
  *   top_k      1..6: experts per request; 1 writes the site index, more write MILORA_ROUTE_SET | mask
  *   route_out  device [B] uint8: route byte per request (row `l` of the caller's route table)
  *   logits_out device [B][7] float or NULL: the seven logits
- *   workspace  device, milora_route_workspace_bytes(B, d, M_tok) bytes
+ *   workspace  device, milora_route_workspace_bytes(B, d, M_tok) bytes, needed by every pooler; its contents
+ *              before the call do not matter (the kernels mark what they hand over with a tag unique to the call
+ *              and wipe the tags they have used, so a call recorded into a HIP graph can be replayed); two calls
+ *              that run at the same time need a workspace each
  * A request whose span leaves [0, M_tok), whose length is < 1 or whose tenant id is out of range
  * gets route MILORA_ROUTE_NONE and NaN logits; the others are unaffected.
  * Errors: EINVAL (null pointers, B/d/T/M_tok < 1, bad enums, w_sa / act_coef missing where needed), ERANGE

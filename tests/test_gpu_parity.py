@@ -78,6 +78,57 @@ def test_route_ragged(dtype, pool, act, d):
     assert torch.equal(route, route2)
 
 
+@pytest.mark.parametrize("pool", ["mean", "max", "last"])
+@pytest.mark.parametrize("B,d,plen", [(19, 1032, (1, 300)), (3, 512, (200, 900)), (40, 4096, (30, 90))])
+def test_route_workspace_needs_no_preparation_and_replays_in_a_graph(pool, B, d, plen):
+    """The router hands slab sums and logit shares between workgroups through the workspace, behind tags: whatever
+    the workspace held before (all ones, random bytes, the tags of an earlier call of another shape) changes nothing,
+    and a recorded launch replayed on new prompts gives what an eager call on a fresh workspace gives.  The three
+    shapes take one slice and several slabs, several slices, and one slab row of many requests."""
+    wl = small(dtype="bf16", d=d, T=6, B=B, prompt_len=plen, pool=pool, act="gelu", tenants="uniform", seed=B + d)
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    ss, sl = ss.to(DEV), sl.to(DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl).to(DEV)
+    nbytes = mb.route_workspace_bytes(B, d, H.shape[0])
+    ref = oracle.route(np_of(H), ss.cpu().numpy(), sl.cpu().numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[pool],
+                       mb.ACT["gelu"])
+    route0, logits0 = mb.milora_route(H, ss, sl, tid, Wr, pool, "gelu",
+                                      workspace=torch.zeros(nbytes, dtype=torch.uint8, device=DEV))
+    assert_routes_match(route0, ref, wl.torch_dtype)
+    np.testing.assert_allclose(to_f64(logits0), ref.logits, atol=2e-5 * max(1.0, np.abs(ref.logits).max()))
+    g = torch.Generator().manual_seed(B)
+    ws = torch.full((nbytes,), 255, dtype=torch.uint8, device=DEV)
+    for fill in ("ones", "random", "other call", "same call"):
+        if fill == "random":
+            ws.copy_(torch.randint(0, 256, (nbytes,), generator=g, dtype=torch.uint8))
+        elif fill == "other call":  # fewer requests on the same workspace leave their tags at other places
+            mb.milora_route(H, ss[:B - 1], sl[:B - 1], tid[:B - 1], Wr, pool, "gelu", workspace=ws)
+        route, logits = mb.milora_route(H, ss, sl, tid, Wr, pool, "gelu", workspace=ws)
+        assert torch.equal(route, route0) and torch.equal(logits, logits0), fill
+
+    Hg = H.clone()
+    route_g = torch.empty(B, dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        mb.milora_route(Hg, ss, sl, tid, Wr, pool, "gelu", route_out=route_g, want_logits=False, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        mb.milora_route(Hg, ss, sl, tid, Wr, pool, "gelu", route_out=route_g, want_logits=False, workspace=ws)
+    for rep in range(4):
+        H_new = torch.roll(H, shifts=7 * (rep + 1), dims=1) * (1.0 + 0.25 * rep)
+        eager, _ = mb.milora_route(H_new, ss, sl, tid, Wr, pool, "gelu")
+        torch.cuda.synchronize()
+        Hg.copy_(H_new)
+        route_g.fill_(77)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(route_g, eager), f"replay {rep}"
+
+
 RATIONAL_COEF = [0.1, 1.0, 0.3, -0.2, 0.05, 0.01, -0.003, 0.5, -0.25, 0.1, 0.02, -0.01]
 
 
