@@ -308,16 +308,17 @@ int milora_pack_weight(const void *src_rowmajor, void *dst_packed, int d1, int d
 /* ------------------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method; for callers that report a kernel's rate against what the
  * GPU sustains rather than against a data-sheet figure).  Both block until their kernels have finished.
- *   milora_measure_matrix_rate: 2 x 32 x iters v_mfma_f32_16x16x32_bf16 per wave on independent
- *     accumulators, four waves per compute unit, nothing else -> *tflops (host pointer).
+ *   milora_measure_matrix_rate: per wave 2 x 32 x iters v_mfma_f32_16x16x32_bf16 (shape 0) or 4 x 8 x iters
+ *     v_mfma_f32_32x32x16_bf16 (shape 1: the same flops in half the instructions and operand reads) on
+ *     independent accumulators, four waves per compute unit, nothing else -> *tflops (host pointer).
  *   milora_measure_read_rate: reads `bytes` (device, 16-byte aligned; use a buffer much larger than the
  *     caches) `reps` times with 16-byte loads -> *gbs (host pointer).
  *   workspace: device, milora_measure_workspace_bytes() bytes.
  * Errors: EINVAL, EWORKSPACE, EHIP.
  */
 size_t milora_measure_workspace_bytes(void);
-int milora_measure_matrix_rate(int iters, void *workspace, size_t workspace_bytes, double *tflops,
-                             void *stream);
+int milora_measure_matrix_rate(int shape, int iters, void *workspace, size_t workspace_bytes,
+                             double *tflops, void *stream);
 int milora_measure_read_rate(const void *buf, size_t bytes, int reps, void *workspace,
                             size_t workspace_bytes, double *gbs, void *stream);
 

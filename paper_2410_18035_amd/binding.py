@@ -104,7 +104,7 @@ def lib() -> ctypes.CDLL:
         L.milora_measure_workspace_bytes.restype = sz
         L.milora_measure_workspace_bytes.argtypes = []
         L.milora_measure_matrix_rate.restype = i32
-        L.milora_measure_matrix_rate.argtypes = [i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
+        L.milora_measure_matrix_rate.argtypes = [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
         L.milora_measure_read_rate.restype = i32
         L.milora_measure_read_rate.argtypes = [vp, sz, i32, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
         _lib = L
@@ -368,11 +368,15 @@ def milora_pack_weight(W: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def milora_measure_matrix_rate(iters: int = 4000, device="cuda:0") -> float:
-    """Sustained bf16 matrix-core rate of the GPU in TFLOP/s (a kernel of nothing but matrix instructions)."""
+MFMA_16X16X32, MFMA_32X32X16 = 0, 1
+
+
+def milora_measure_matrix_rate(iters: int = 4000, device="cuda:0", shape: int = MFMA_16X16X32) -> float:
+    """Sustained bf16 matrix-core rate of the GPU in TFLOP/s (a kernel of nothing but matrix instructions of
+    the given shape)."""
     ws = torch.empty(lib().milora_measure_workspace_bytes(), dtype=torch.uint8, device=device)
     out = ctypes.c_double(0.0)
-    rc = lib().milora_measure_matrix_rate(iters, _dev(ws), ws.numel(), ctypes.byref(out), _stream())
+    rc = lib().milora_measure_matrix_rate(shape, iters, _dev(ws), ws.numel(), ctypes.byref(out), _stream())
     if rc:
         raise MiloraError(rc, "milora_measure_matrix_rate")
     return out.value

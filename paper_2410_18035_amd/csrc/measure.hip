@@ -13,16 +13,29 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kAccs = 32;
 
-__global__ void __launch_bounds__(256, 1) mfma_rate_kernel(float* out, int iters) {
+// Operand values: small integers (few bits change between lanes and elements), or, with `mixed`, values spread
+// over [-1, 1) with every mantissa bit in use - what weights and activations look like, and what the matrix cores
+// draw more power for.
+__device__ __forceinline__ void rate_operands(bf16x8& a, bf16x8& b, int mixed) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (mixed) {
+      const uint32_t ha = (threadIdx.x * 8u + i + 1u) * 2654435761u, hb = (threadIdx.x * 8u + i + 77u) * 2246822519u;
+      a[i] = (__bf16)((float)(int)(ha >> 8) * (1.0f / 8388608.0f) - 1.0f);
+      b[i] = (__bf16)((float)(int)(hb >> 8) * (1.0f / 8388608.0f) - 1.0f);
+    } else {
+      a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
+      b[i] = (__bf16)(float)(i & 1);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256, 1) mfma_rate_kernel(float* out, int iters, int mixed) {
   f32x4 acc[kAccs];
 #pragma unroll
   for (int i = 0; i < kAccs; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   bf16x8 a, b;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
-    b[i] = (__bf16)(float)(i & 1);
-  }
+  rate_operands(a, b, mixed);
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < kAccs; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
@@ -32,6 +45,35 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(float* out, int iters
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < kAccs; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int kAccs32 = 8;
+
+// The same with v_mfma_f32_32x32x16_bf16: twice the flops per instruction and per operand register read.
+__global__ void __launch_bounds__(256, 1) mfma32_rate_kernel(float* out, int iters, int mixed) {
+  f32x16 acc[kAccs32];
+#pragma unroll
+  for (int i = 0; i < kAccs32; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  bf16x8 a, b;
+  rate_operands(a, b, mixed);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+#pragma unroll
+      for (int i = 0; i < kAccs32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < kAccs32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i], 0, 0, 0);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kAccs32; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
   out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
@@ -61,9 +103,11 @@ using namespace milora;
 
 extern "C" size_t milora_measure_workspace_bytes(void) { return (size_t)1024 * 256 * sizeof(float); }
 
-extern "C" int milora_measure_matrix_rate(int iters, void* workspace, size_t workspace_bytes, double* tflops,
+extern "C" int milora_measure_matrix_rate(int shape, int iters, void* workspace, size_t workspace_bytes, double* tflops,
                                         void* stream) {
-  if (iters < 1 || !tflops) return MILORA_EINVAL;
+  if (iters < 1 || !tflops || shape < 0 || shape > 3) return MILORA_EINVAL;
+  const int mixed = shape >> 1;
+  shape &= 1;
   if (!workspace || workspace_bytes < milora_measure_workspace_bytes()) return MILORA_EWORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   int dev = 0, cus = 0;
@@ -73,9 +117,10 @@ extern "C" int milora_measure_matrix_rate(int iters, void* workspace, size_t wor
   hipEvent_t e0, e1;
   MILORA_HIP(hipEventCreate(&e0));
   MILORA_HIP(hipEventCreate(&e1));
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, st, (float*)workspace, iters < 64 ? iters : 64);
+  auto* kernel = shape == 0 ? mfma_rate_kernel : mfma32_rate_kernel;
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, (float*)workspace, iters < 64 ? iters : 64, mixed);
   hipEventRecord(e0, st);
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, st, (float*)workspace, iters);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, (float*)workspace, iters, mixed);
   hipEventRecord(e1, st);
   hipError_t e = hipEventSynchronize(e1);
   float ms = 0.f;
@@ -83,7 +128,9 @@ extern "C" int milora_measure_matrix_rate(int iters, void* workspace, size_t wor
   hipEventDestroy(e0);
   hipEventDestroy(e1);
   if (e != hipSuccess) return hip_fail(e);
+  // both kernels issue 64 instructions' worth of 16x16x32 per wave and iteration: 32 of twice the size in the second
   const double flops = (double)grid * 4.0 * (double)iters * (2.0 * kAccs) * (2.0 * 16 * 16 * 32);
+  static_assert(2 * 2 * kAccs32 * 32 * 32 * 16 == 2 * kAccs * 16 * 16 * 32, "same flops per iteration");
   *tflops = flops / ((double)ms * 1e-3) / 1e12;
   return check_launch();
 }

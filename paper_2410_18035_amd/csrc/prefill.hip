@@ -2,11 +2,14 @@
 // Sec. 3.3): Y = X W^T + bias + (X W^A) W^B for the rows whose request is routed to this site.
 //
 // One workgroup of four waves computes a 256 x 256 tile of Y with the bf16 matrix cores
-// (v_mfma_f32_16x16x32_bf16, fp32 accumulators, 128 x 128 per wave).  X and W are both contiguous along the
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulators, 128 x 128 per wave; a kernel of nothing but this instruction
+// sustains 2.3-2.4 PFLOP/s on the chip, one of nothing but the 16x16x32 form 1.45-1.5).  X and W are both contiguous along the
 // reduction index: 16-row x 64-k blocks of either are copied from global memory straight into LDS
 // (global_load_lds_dwordx4, no registers; whole 128-byte lines per row), in a ring of five half steps of
-// 32 KB (three in flight while two are read), and read back as matrix-core operands with one conflict-free
-// 16-byte LDS load per lane, block and k half.
+// 32 KB, and read back as matrix-core operands with one conflict-free 16-byte LDS load per lane, pair of blocks
+// and 16 k.  A step's operands are all in registers after a quarter of its matrix work; its ring slots are
+// refilled from there on, so that nearly the whole LDS is data on its way (the copies are bound by latency:
+// bytes in flight over about two microseconds).
 // The LoRA term enters as extra k steps: t = X W^A (fp32, computed beforehand) split into two bf16 halves
 // (hi + lo, so nothing of t's precision is lost) against W^B of the tenant, masked to that tenant's rows.
 // Bias is added and the result rounded once at the store.
@@ -19,6 +22,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 // Adapter matrices are reached through pointer tables read at run time; telling the compiler that they lie in
 // global memory keeps their loads off the counter the LDS reads wait on.
 typedef __attribute__((address_space(1))) const bf16_t gbf16;
@@ -31,7 +35,17 @@ constexpr int kBlockBytes = 16 * kTK * 2;                 // 16 rows x 64 k: 2 K
 constexpr int kHalfBytes = (kBlocksM + kBlocksN) / 2 * kBlockBytes;  // 8 X blocks + 8 W blocks: 32 KiB
 constexpr int kHalves = 5;                                // ring of half steps
 constexpr int kLdsBytesP = kHalves * kHalfBytes;
-constexpr int kAccTilesRows = 6;
+constexpr int kAccTilesRows = 3;
+// Where the sixteen copy instructions of a k step sit among its 64 matrix instructions: those of the first half
+// after instructions 0, kCopyAStride, ..., those of the second half from instruction kCopyB0 on (16 or later: the
+// slot they fill is read until then).
+#ifndef PF_CA
+#define PF_CA 2
+#define PF_CB0 16
+#define PF_CBS 3
+#endif
+constexpr int kCopyAStride = PF_CA, kCopyB0 = PF_CB0, kCopyBStride = PF_CBS;
+static_assert(kCopyB0 >= 16 && 7 * kCopyAStride < kCopyB0 && kCopyB0 + 7 * kCopyBStride < 64, "copy positions");
 constexpr int kShrinkSplit = kPrefillShrinkParts;  // the shrink's reduction is cut into this many parts, one workgroup each
 constexpr int kGroupM = 4;  // consecutive workgroups of an XCD walk 4 row tiles of one column tile
 
@@ -68,19 +82,6 @@ __device__ __forceinline__ void copy_to_lds(const void* base, uint32_t voff, uin
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
-}
-
-// One k step of 32 for the wave's 128 x 128 part: operand blocks from LDS, 64 matrix-core instructions.
-__device__ __forceinline__ void mma_step(const unsigned char* sa, const unsigned char* sb, f32x4 (&acc)[8][8]) {
-  bf16x8 a[8], b[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) a[i] = *(const bf16x8*)(sa + i * kBlockBytes);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) b[j] = *(const bf16x8*)(sb + j * kBlockBytes);
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
 }
 
 __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
@@ -127,82 +128,112 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
     }
   const uint32_t dst_in_half = (uint32_t)((is_w ? 8 : 0) + (wave & 1) * 4) * kBlockBytes;
   // half H = 2 * (k step) + hh lives in ring slot H % kHalves
-  auto issue = [&](int kt, int hh, int slot) __attribute__((always_inline)) {
+  // copy j (0..7) of a half; a wave's eight copies of a half are spread between its matrix instructions: issued
+  // back to back they would hold the wave at the issue of the memory instructions while the matrix cores idle
+  auto issue_one = [&](int kt, int hh, int slot, int j) __attribute__((always_inline)) {
     const int kk = kt < KT ? kt : KT - 1;  // past the end: re-read the last step into a slot nobody reads
     const unsigned char* b = src + (size_t)kk * (kTK * 2);
     const uint32_t dst = lds0 + slot * kHalfBytes + dst_in_half;
+    copy_to_lds(b, voff[hh][j], dst + j * 1024);
+  };
+  auto issue = [&](int kt, int hh, int slot) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      copy_to_lds(b, voff[hh][j], dst + j * 1024);
-    }
+    for (int j = 0; j < 8; ++j) issue_one(kt, hh, slot, j);
   };
 
-  f32x4 acc[8][8];
+  // acc[i][j]: rows 32 i .. 32 i + 31 of the wave's X part against rows 32 j .. of its W part
+  f32x16 acc[4][4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // operand read: lane l takes row l % 16 and the 16 bytes of k group l / 16 of either k half of a block
-  const int rrow = lane & 15;
-  const int rd0 = rrow * 128 + ((((lane >> 4)) ^ (rrow & 7)) << 4);
-  const int rd1 = rrow * 128 + ((((lane >> 4) + 4) ^ (rrow & 7)) << 4);
+  // operand read: lane l takes row l % 32 of a pair of 16-row blocks and the 16 bytes of k group 2 ks + l / 32
+  // (ks = 0..3: the four 16-k sub-steps of a block's 64 k)
+  const int rrow = lane & 31;
+  int rd[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    rd[ks] = (rrow >> 4) * kBlockBytes + (rrow & 15) * 128 + (((2 * ks + (lane >> 5)) ^ (rrow & 7)) << 4);
   const unsigned char* wbase = lds + (kBlocksM / 2) * kBlockBytes;
-  auto mma64 = [&](int slot_x, int slot_w) __attribute__((always_inline)) {
+  // One k step of 64 for the wave's 128 x 128 part: 64 matrix instructions, number q = 16 ks + 4 i + j.  The
+  // operand reads come early: the sixteen of the first two sub-steps, then the other sixteen between the matrix
+  // instructions of the first sub-step.  `mid` runs after instruction 15, once every wave of the workgroup has
+  // its operands in registers: the step's two ring slots are free from there on.  copy(q) runs after instruction q.
+  auto mma64 = [&](int slot_x, int slot_w, auto mid, auto copy) __attribute__((always_inline)) {
     const unsigned char* sa = lds + slot_x * kHalfBytes;
     const unsigned char* sb = wbase + slot_w * kHalfBytes;
-    // both k halves in one scheduling region: the operand reads of the second half are issued between the
-    // matrix instructions of the first
-    bf16x8 a0[8], b0[8], a1[8], b1[8];
+    bf16x8 a[4][4], b[4][4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a0[i] = *(const bf16x8*)(sa + rd0 + i * kBlockBytes);
+    for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) b0[j] = *(const bf16x8*)(sb + rd0 + j * kBlockBytes);
+      for (int i = 0; i < 4; ++i) a[ks][i] = *(const bf16x8*)(sa + rd[ks] + i * 2 * kBlockBytes);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a1[i] = *(const bf16x8*)(sa + rd1 + i * kBlockBytes);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) b1[j] = *(const bf16x8*)(sb + rd1 + j * kBlockBytes);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0[j], a0[i], acc[i][j], 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1[j], a1[i], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+      for (int j = 0; j < 4; ++j) b[ks][j] = *(const bf16x8*)(sb + rd[ks] + j * 2 * kBlockBytes);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0][q & 3], a[0][q >> 2], acc[q >> 2][q & 3], 0, 0, 0);
+      const int ks = 2 + (q >> 3), e = q & 3;
+      if (q & 4) b[ks][e] = *(const bf16x8*)(sb + rd[ks] + e * 2 * kBlockBytes);
+      else a[ks][e] = *(const bf16x8*)(sa + rd[ks] + e * 2 * kBlockBytes);
+      copy(q);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 64, 0);
+    mid();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 16; q < 64; ++q) {
+      acc[(q >> 2) & 3][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[q >> 4][q & 3], a[q >> 4][(q >> 2) & 3],
+                                                                         acc[(q >> 2) & 3][q & 3], 0, 0, 0);
+      copy(q);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
 
   issue(0, 0, 0);
   issue(0, 1, 1);
   issue(1, 0, 2);
-  // 48 of the 64 accumulator tiles in the accumulation registers, 16 in ordinary ones: with all 256 in the
+  issue(1, 1, 3);
+  // 12 of the 16 accumulator tiles in the accumulation registers, 4 in ordinary ones: with all 256 in the
   // accumulation file the compiler has no spare tile there and shuffles tiles between the files in the loop
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < 4; ++j) {
       if (i < kAccTilesRows) asm volatile("" : "+a"(acc[i][j]));
       else asm volatile("" : "+v"(acc[i][j]));
     }
+  // The ring: halves 2 kt and 2 kt + 1 (this step) are read, the two of the next step are on their way, the
+  // fifth slot takes the first half of the step after next at once and the second half goes into this step's
+  // first slot as soon as every wave has taken its operands out: a copy has between one and three quarters and
+  // two whole steps of matrix work to arrive.
   int h0 = 0;  // ring slot of half 0 of the current step
   for (int kt = 0; kt < KT; ++kt) {
     const int h1 = h0 + 1 >= kHalves ? h0 + 1 - kHalves : h0 + 1;
     const int h2 = h0 + 2 >= kHalves ? h0 + 2 - kHalves : h0 + 2;
-    const int h3 = h0 + 3 >= kHalves ? h0 + 3 - kHalves : h0 + 3;
     const int h4 = h0 + 4 >= kHalves ? h0 + 4 - kHalves : h0 + 4;
-    wait_vm<8>();                   // all but the half issued last have landed: both halves of this step
-    __builtin_amdgcn_s_barrier();   // for every wave; and all waves are done reading the step before
+    wait_vm<16>();                  // all but the two halves issued last have landed: both halves of this step
+    __builtin_amdgcn_s_barrier();   // for every wave
     asm volatile("" ::: "memory");
-    issue(kt + 1, 1, h3);
-    issue(kt + 2, 0, h4);
-    mma64(wm ? h1 : h0, wn ? h1 : h0);
+    mma64(
+        wm ? h1 : h0, wn ? h1 : h0,
+        [&]() __attribute__((always_inline)) {
+          __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's operand reads have returned
+          __builtin_amdgcn_s_barrier();        // and every other wave's
+          asm volatile("" ::: "memory");
+        },
+        [&](int q) __attribute__((always_inline)) {
+          // first half of the step after next into the free slot, second half into this step's first slot
+          if (q < kCopyB0) {
+            if (q % kCopyAStride == 0 && q / kCopyAStride < 8) issue_one(kt + 2, 0, h4, q / kCopyAStride);
+          } else if ((q - kCopyB0) % kCopyBStride == 0 && (q - kCopyB0) / kCopyBStride < 8) {
+            issue_one(kt + 2, 1, h0, (q - kCopyB0) / kCopyBStride);
+          }
+        });
     asm volatile("" ::: "memory");
     h0 = h2;
   }
@@ -299,30 +330,34 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
         *(u32x4*)(lds + (kBlocksM / 2) * kBlockBytes + o_lo) = wb;
       }
       __syncthreads();
-      mma64(wm, wn);
+      mma64(wm, wn, []() {}, [](int) {});
       __syncthreads();
     }
     last = cur;
   }
 
-  // ---- bias, one rounding, store: a lane holds 4 consecutive columns of one row per 16 x 16 tile ----------
+  // ---- bias, one rounding, store: of a 32 x 32 tile a lane holds row l % 32 and, in registers 4 g .. 4 g + 3, the
+  // columns 8 g + 4 (l / 32) .. + 3
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int n = n0 + wn * 128 + j * 16 + (lane >> 4) * 4;
-    if (n >= p.d2) continue;
-    float bv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (p.bias) {
+  for (int j = 0; j < 4; ++j) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) bv[e] = bf16_to_f32(p.bias[n + e]);
-    }
+    for (int g = 0; g < 4; ++g) {
+      const int n = n0 + wn * 128 + j * 32 + g * 8 + (lane >> 5) * 4;
+      if (n >= p.d2) continue;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (p.bias) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int64_t m = m0 + wm * 128 + i * 16 + (lane & 15);
-      if (m >= p.M) continue;
-      u32x2 v;
-      v[0] = pack_bf16x2(acc[i][j][0] + bv[0], acc[i][j][1] + bv[1]);
-      v[1] = pack_bf16x2(acc[i][j][2] + bv[2], acc[i][j][3] + bv[3]);
-      *(u32x2*)(p.Y + (size_t)m * p.d2 + n) = v;
+        for (int e = 0; e < 4; ++e) bv[e] = bf16_to_f32(p.bias[n + e]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int64_t m = m0 + wm * 128 + i * 32 + (lane & 31);
+        if (m >= p.M) continue;
+        u32x2 v;
+        v[0] = pack_bf16x2(acc[i][j][4 * g] + bv[0], acc[i][j][4 * g + 1] + bv[1]);
+        v[1] = pack_bf16x2(acc[i][j][4 * g + 2] + bv[2], acc[i][j][4 * g + 3] + bv[3]);
+        *(u32x2*)(p.Y + (size_t)m * p.d2 + n) = v;
+      }
     }
   }
 }

@@ -390,7 +390,9 @@ def test_measurement_helpers_report_plausible_rates():
     buf = torch.empty(1 << 29, dtype=torch.uint8, device=DEV).zero_()
     gbs = mb.milora_measure_read_rate(buf, reps=3)
     tf = mb.milora_measure_matrix_rate(500, DEV)
-    assert 500 < gbs < 20000 and 100 < tf < 5000
+    tf32 = mb.milora_measure_matrix_rate(500, DEV, shape=mb.MFMA_32X32X16)
+    print(f"read {gbs:.0f} GB/s, matrix cores 16x16x32 {tf:.0f} TFLOP/s, 32x32x16 {tf32:.0f} TFLOP/s")
+    assert 500 < gbs < 20000 and 100 < tf < 5000 and 100 < tf32 < 5000
 
 
 def test_prefill_shape_sampled_rows_full_size():
