@@ -450,7 +450,10 @@ def main():
     # ---- what the GPU sustains on the two bounding resources, and the many-row leg ------------------
     big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     ceilings = {"hbm_read_gbs": round(mb.milora_measure_read_rate(big, reps=5), 1),
-                "mfma_bf16_tflops": round(mb.milora_measure_matrix_rate(4000, dev), 1)}
+                "mfma_bf16_tflops": round(mb.milora_measure_matrix_rate(
+                    4000, dev, shape=mb.MFMA_32X32X16 + mb.MFMA_MIXED_OPERANDS), 1),
+                "mfma_bf16_tflops_small_integer_operands": round(mb.milora_measure_matrix_rate(
+                    4000, dev, shape=mb.MFMA_32X32X16), 1)}
     del big
     roofline["frac_of_measured_read_rate"] = round(achieved / ceilings["hbm_read_gbs"], 4)
     prefill = None

@@ -310,7 +310,9 @@ int milora_pack_weight(const void *src_rowmajor, void *dst_packed, int d1, int d
  * GPU sustains rather than against a data-sheet figure).  Both block until their kernels have finished.
  *   milora_measure_matrix_rate: per wave 2 x 32 x iters v_mfma_f32_16x16x32_bf16 (shape 0) or 4 x 8 x iters
  *     v_mfma_f32_32x32x16_bf16 (shape 1: the same flops in half the instructions and operand reads) on
- *     independent accumulators, four waves per compute unit, nothing else -> *tflops (host pointer).
+ *     independent accumulators, four waves per compute unit, nothing else -> *tflops (host pointer).  Operands are
+ *     small integers; shape + 2 takes operands spread over [-1, 1) with every mantissa bit in use (what weights
+ *     and activations look like: the matrix cores draw more power for them and the clock gives way).
  *   milora_measure_read_rate: reads `bytes` (device, 16-byte aligned; use a buffer much larger than the
  *     caches) `reps` times with 16-byte loads -> *gbs (host pointer).
  *   workspace: device, milora_measure_workspace_bytes() bytes.

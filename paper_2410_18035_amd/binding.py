@@ -369,6 +369,7 @@ def milora_pack_weight(W: torch.Tensor) -> torch.Tensor:
 
 
 MFMA_16X16X32, MFMA_32X32X16 = 0, 1
+MFMA_MIXED_OPERANDS = 2  # added to a shape: operands that use every mantissa bit
 
 
 def milora_measure_matrix_rate(iters: int = 4000, device="cuda:0", shape: int = MFMA_16X16X32) -> float:
