@@ -47,6 +47,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kMaxStages = 12;
 constexpr int kMaxRows = MILORA_MAX_DECODE_BATCH;
 constexpr int kMaxGrid = 1024;          // workgroups the barrier flags are sized for
+constexpr int kMaxSplitGrid = 512;      // workgroups of a ksplit stage at most (their partial-tile table is sized for it)
 constexpr int kShrinkChunk = 512;       // reduction rows per LoRA shrink item
 constexpr int kSteady = 8;              // weight loads per stream wave in flight between stage ends
 constexpr int kSpinLimit = 1 << 22;     // polls before a bounded wait gives up (unless the caller set another limit)
@@ -76,6 +77,9 @@ struct Stage {
   int N[3], site[3];
   int unit0, units;  // this stage covers units [unit0, unit0 + units) of the level (tiles, or gate/up tile pairs),
   int cap;           // workgroup g taking units [g * cap, (g + 1) * cap) of them
+  int ksplit;        // 2: workgroups 2 j and 2 j + 1 stream tiles 2 j and 2 j + 1 over one half of the reduction each
+                     // (half the input rows per workgroup), swap the partial tile of the other's output tile through
+                     // memory, and workgroup 2 j + h finishes tile 2 j + h.  One-site stages without normalisation.
   const bf16_t* bias[3];
   const bf16_t* resid_bf16;
   const float* resid_f32;
@@ -110,6 +114,8 @@ struct Params {
   int* dready;    // wide kernel: [level parity][site position][slab of 256 columns][row] tag of the LoRA term stored there
   int delta_odd, slabs_max;
   int* flags;     // [kMaxGrid] grid barrier flags, monotone
+  float* xpart;   // [kMaxSplitGrid][row tiles][256] partial tile a workgroup of a ksplit stage hands to its partner
+  int* xflag;     // [kMaxGrid] launch epoch * 16 + stage + 1 of the partial tile stored there
   int* status;    // set to 1 when a bounded wait ran out
   int spin_limit; // polls before a bounded wait gives up
   long long* trace;  // tracing launches only: [workgroup][stage][wave][8] time stamps (100 MHz clock), see TS
@@ -179,6 +185,13 @@ __device__ __forceinline__ void st_through(u32x4* p, u32x4 v) {
 }
 __device__ __forceinline__ void st_through(f32x4* p, f32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+}
+// One 16-byte load that bypasses the caches (data stored through by another workgroup in this launch), complete
+// when the function returns.
+__device__ __forceinline__ f32x4 ld_through1(const f32x4* p) {
+  f32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p) : "memory");
+  return v;
 }
 // LDS flags between the waves of a workgroup.  LDS operations of a wave execute in order, so a flag
 // written after data is seen after the data; the compiler is kept from moving accesses across.
@@ -392,7 +405,19 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   // ---- this workgroup's tiles in every stage -----------------------------------------------------------
   if (tid < kMaxStages * 8) {
     const int L = tid >> 3, a = tid & 7;
-    if (L < p.n_stages) {
+    if (L < p.n_stages && p.st[L].ksplit == 2) {
+      // tiles 2 j, 2 j + 1 over half wg % 2 of the reduction; the tail waves see one tile: the one this workgroup finishes
+      const Stage& s = p.st[L];
+      const bool has = 2 * (wg >> 1) + 1 < s.units;
+      if (a == 0) c.ns[L] = has ? 2 : 0;
+      if (a < 2 && has) {
+        const int tile = s.unit0 + 2 * (wg >> 1) + a;
+        const unsigned long long kt_half = (unsigned long long)(s.K >> 6);
+        c.tb_ptr[L][a] = (unsigned long long)(uintptr_t)s.W[0] + ((unsigned long long)tile * (s.K >> 5) + (wg & 1) * kt_half) * 1024ull;
+        c.tb_seg[L][a] = a == 0 ? 0 : -1;
+        c.tb_tile[L][a] = s.unit0 + 2 * (wg >> 1) + (wg & 1);
+      }
+    } else if (L < p.n_stages) {
       const Stage& s = p.st[L];
       const int f0 = wg * s.cap < s.units ? wg * s.cap : s.units, f1 = f0 + s.cap < s.units ? f0 + s.cap : s.units;
       const int u0 = s.unit0 + f0, u1 = s.unit0 + f1;
@@ -463,6 +488,9 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   // A stage's reduction is cut into chunks of kSW k blocks, one per stream wave.  Every workgroup walks the
   // chunks in its own rotation (start_of): the workgroups of an XCD all read the same input rows, and in
   // lockstep they would all hit the same few L2 channels.
+  // k blocks of a stage that this workgroup walks (half of them in a ksplit stage) and the first of them
+  auto kt_of = [&](const Stage& sg) __attribute__((always_inline)) -> int { return sg.ksplit == 2 ? sg.K >> 6 : sg.K >> 5; };
+  auto kb0_of = [&](const Stage& sg) __attribute__((always_inline)) -> int { return sg.ksplit == 2 ? (wg & 1) * (sg.K >> 6) : 0; };
   auto chunks_of = [&](int ns, int kt) __attribute__((always_inline)) -> int { return ns > 0 ? (kt + kSW - 1) / kSW : 0; };
   auto rounds_of = [&](int ns, int nch) __attribute__((always_inline)) -> int { return (ns * nch + D - 1) / D; };
   auto start_of = [&](int nch) __attribute__((always_inline)) -> int {
@@ -517,7 +545,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         ++p_stage;
         if (p_stage >= p.n_stages) break;
         ns = __builtin_amdgcn_readfirstlane(c.ns[p_stage]);
-        kt = p.st[p_stage].K >> 5;
+        kt = kt_of(p.st[p_stage]);
         nch = chunks_of(ns, kt);
         left = rounds_of(ns, nch) * D;
         if (left > 0) break;
@@ -562,7 +590,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     int lbase[2] = {0, 0};   // ... and how many of them each loader wave brought
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
-      const int K = sg.K, KT = K >> 5;
+      const int KT = kt_of(sg);
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
       const int NCH = chunks_of(NS, KT);
       const int NBUF = nbuf_of(NS);
@@ -894,6 +922,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
   int lcount = 0;  // chunks this wave has brought in the earlier stages
   auto load_input = [&](const int L, const Stage& sg, const int KT, const int NS, const int NCH, const int NBUF,
                         const int nseq, const int lj) __attribute__((always_inline)) {
+    const int kb_first = kb0_of(sg);  // the stage's k blocks this workgroup walks are kb_first .. kb_first + KT - 1
     if (NS > 0) {
         // A block is the 1 KiB operand of one k block and one 16-row tile; lane l of the consumer holds
         // (row l % 16, k group l / 16).  The copies go from global memory straight into LDS (lane l of a wave load
@@ -949,7 +978,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             const int kb = kb0 + pos < KT ? kb0 + pos : KT - 1;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-              __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xb + (size_t)kb * kstep + loff[mt]),
+              __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xb + (size_t)(kb_first + kb) * kstep + loff[mt]),
                                                (__attribute__((address_space(3))) void*)(dst + ((pos * MT + mt) << 10)), 16, 0, 0);
           }
           // with `depth` chunks in flight the oldest has landed once at most (depth - 1) chunks of loads are out
@@ -975,8 +1004,9 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     // ===================================== input loader =====================================
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
-      const int K = sg.K, KT = K >> 5;
+      const int KT = kt_of(sg);
       const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
+      const int NSo = sg.ksplit == 2 ? NS >> 1 : NS;  // tiles this workgroup finishes
       const int NCH = chunks_of(NS, KT);
       const int NBUF = nbuf_of(NS);
       TS(0);
@@ -988,10 +1018,10 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       nseq += NCH;
       // ---- stage end: the LoRA wave has added the LoRA terms to the sums ---------------------------------------
       float pre[8];
-      glue_prefetch(L, sg, NS, 0, pre);
+      glue_prefetch(L, sg, NSo, 0, pre);
       spin_until([&]() { return ld_lds(&c.tail_go) >= L + 1; });
       TS(4);
-      glue(L, sg, NS, 0, pre);
+      glue(L, sg, NSo, 0, pre);
       wait_all_mem();
       TS(5);
       st_lds(&c.tail_done, L + 1);
@@ -1002,7 +1032,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     for (int L = 0; L < p.n_stages; ++L) {
       const Stage& sg = p.st[L];
       const int K = sg.K;
-      const int NS = __builtin_amdgcn_readfirstlane(c.ns[L]);
+      const int NSs = __builtin_amdgcn_readfirstlane(c.ns[L]);  // tiles this workgroup streams
+      const int NS = sg.ksplit == 2 ? NSs >> 1 : NSs;           // tiles it finishes
       const int NC = shrink_chunks(K);
       TS(0);
       if (sg.lora_shrink) lvl_tag = epoch * 16 + L + 1;  // a slot can serve several levels of one launch
@@ -1034,12 +1065,12 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         TS(2);
       }
       if (kLoaders > 1) {
-        const int KT = K >> 5;
+        const int KT = kt_of(sg);
         if (sg.sync_before && L > 0 && !(p.lora && sg.lora_shrink)) {
           if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
         }
-        load_input(L, sg, KT, NS, chunks_of(NS, KT), nbuf_of(NS), nseq, 1);
-        nseq += chunks_of(NS, KT);
+        load_input(L, sg, KT, NSs, chunks_of(NSs, KT), nbuf_of(NSs), nseq, 1);
+        nseq += chunks_of(NSs, KT);
       }
       // ---- rows whose LoRA term lands in this workgroup's tiles; their expand is formed ahead of the stage end ----
       int cnt = 0, npre = 0;
@@ -1091,6 +1122,30 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       // ---- stage end: all six stream waves have summed their part of the tiles ---------------------------------
       spin_until([&]() { return ld_lds(&c.sum_cnt) >= (L + 1) * kSW; });
       TS(5);
+      if (sg.ksplit == 2 && NSs > 0) {
+        // `red` holds this workgroup's half of the sums of tiles 2 j and 2 j + 1.  The half of the tile the partner
+        // finishes goes to memory, stored through and acknowledged before the flag; the partner's half of this
+        // workgroup's tile comes back the same way.  Sum = first half of the reduction + second half, on both sides.
+        constexpr int kTileF4 = MT * 64;  // 16-byte pieces of a tile's sums
+        const int h = wg & 1, partner = wg ^ 1;
+        const int tag = epoch * 16 + L + 1;
+        f32x4* const mine = reinterpret_cast<f32x4*>(p.xpart) + (size_t)wg * kTileF4;
+        const f32x4* const theirs = reinterpret_cast<const f32x4*>(p.xpart) + (size_t)partner * kTileF4;
+        const f32x4* const send = reinterpret_cast<const f32x4*>(red) + (1 - h) * kTileF4;
+        for (int e = lane; e < kTileF4; e += 64) st_through(mine + e, send[e]);
+        wait_all_mem();
+        if (lane == 0) st_agent(p.xflag + wg, tag);
+        spin_until([&]() { return ld_agent(p.xflag + partner) == tag; });
+        f32x4* const keep = reinterpret_cast<f32x4*>(red) + h * kTileF4;
+        f32x4* const out = reinterpret_cast<f32x4*>(red);
+        for (int e = lane; e < kTileF4; e += 64) {
+          const f32x4 got = ld_through1(theirs + e);
+          const f32x4 own = keep[e];
+          out[e] = h == 0 ? own + got : got + own;
+        }
+        wave_sync();
+        TS(8);
+      }
       for (int m = lane; m < MT * 16; m += 64) {
         float ssq = 0.f;
 #pragma unroll
@@ -2017,7 +2072,7 @@ int wide_segments(int MT, int d, int F) {
 
 void reset_stage(Stage& s) {
   s.X = nullptr; s.ldx = 0; s.K = 0; s.x_packed = 0; s.out_pk = nullptr; s.n_seg = 0; s.pair = 0; s.norm = 0; s.sync_before = 0; s.lora_shrink = 0; s.tpos0 = 0;
-  s.unit0 = 0; s.units = 0; s.cap = 1;
+  s.unit0 = 0; s.units = 0; s.cap = 1; s.ksplit = 1;
   for (int i = 0; i < 3; ++i) {
     s.W[i] = nullptr; s.N[i] = 0; s.site[i] = -1; s.bias[i] = nullptr; s.out[i] = nullptr; s.ld_out[i] = 0;
   }
@@ -2053,6 +2108,21 @@ int plan_level(int left, int G, int per_unit, int ns_max, int depth, int* caps, 
 // the weights of their next one).  Returns false when the launch would need more stages than it has.
 bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_max) {
   const int per_unit = level.pair ? 2 : 1;
+  if (level.ksplit == 2) {
+    // one stage: pairs of workgroups share pairs of tiles, each taking one half of the reduction
+    const bool fits = level.n_seg == 1 && !level.pair && !level.norm && units_total % 2 == 0 && units_total <= (G & ~1) && units_total <= kMaxSplitGrid &&
+                      (level.K >> 5) % 2 == 0 && ns_max % 2 == 0 && p.xpart != nullptr;
+    if (fits) {
+      if (p.n_stages >= kMaxStages) return false;
+      Stage& s = p.st[p.n_stages++];
+      s = level;
+      s.unit0 = 0;
+      s.units = units_total;
+      s.cap = 1;
+      s.lora_shrink = 1;
+      return true;
+    }
+  }
   int caps[kMaxStages], n_caps = 0;
   if (plan_level(units_total, G, per_unit, ns_max, 0, caps, &n_caps) >= (1 << 30)) return false;
   int left = units_total, u = 0;
@@ -2060,6 +2130,7 @@ bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_ma
     if (p.n_stages >= kMaxStages) return false;
     Stage& s = p.st[p.n_stages++];
     s = level;
+    s.ksplit = 1;
     s.unit0 = u;
     s.units = left < caps[i] * G ? left : caps[i] * G;
     s.cap = caps[i];
@@ -2075,6 +2146,8 @@ bool push_level(Params& p, const Stage& level, int units_total, int G, int ns_ma
 struct DecodeWs {
   int* flags;      // [kMaxGrid] barrier flags; zero before the first launch, then owned by the kernels
   int* status;
+  int* xflag;      // [kMaxGrid] flags of the partial tiles swapped inside ksplit stages; zero before the first launch
+  float* xpart;    // [kMaxSplitGrid][row tiles][256] those tiles
   int* tready;     // [kSlotsPerRow kMaxRows] per shrink slot: epoch of the launch that published it
   int* tcount;     // [kSlotsPerRow kMaxRows] partials written so far (zero between launches)
   float* tfin;     // [kSlotsPerRow M][r_max] published shrinks
@@ -2097,7 +2170,7 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max, bool wide =
   const int big = F > d ? F : d;
   size_t off = 0;
   auto take = [&](size_t n) { size_t o = off; off += align_up(n, 256); return o; };
-  const size_t o_fl = take((size_t)(kMaxGrid + 64) * sizeof(int));
+  const size_t o_fl = take((size_t)(2 * kMaxGrid + 64) * sizeof(int));
   const size_t o_p = take((size_t)kMaxRows * 2 * kSlotsPerRow * sizeof(int));  // at a fixed place whatever M is: the counters must read zero
   const size_t o_tf = take((size_t)kSlotsPerRow * M * r_max * sizeof(float));
   const size_t o_t = take((size_t)kSlotsPerRow * M * shrink_chunks(big) * r_max * sizeof(float));
@@ -2106,6 +2179,7 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max, bool wide =
   const size_t o_v = take((size_t)rows * d * sizeof(bf16_t));
   const size_t o_hb = take((size_t)rows * d * sizeof(bf16_t));
   const size_t o_m = take((size_t)rows * F * sizeof(bf16_t));
+  const size_t o_xp = M <= 32 ? take((size_t)kMaxSplitGrid * rows * 16 * sizeof(float)) : 0;  // ksplit stages: up to 32 rows only
   size_t o_sf = 0, o_ss = 0, o_wp = 0, o_tp = 0, o_dr = 0, o_dt = 0;
   // LoRA term tiles of the wide kernel: the sites of an even level (q,k,v or gate,up) side by side, then those of an
   // odd level (o or down); 256-column slabs of the widest site
@@ -2122,7 +2196,7 @@ DecodeWs carve_decode_ws(void* base, int M, int d, int F, int r_max, bool wide =
   }
   char* b = (char*)base;
   int* fl = (int*)(b + o_fl);
-  return DecodeWs{fl, fl + kMaxGrid, (int*)(b + o_p), (int*)(b + o_p) + kSlotsPerRow * kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
+  return DecodeWs{fl, fl + kMaxGrid, fl + kMaxGrid + 64, M <= 32 ? (float*)(b + o_xp) : nullptr, (int*)(b + o_p), (int*)(b + o_p) + kSlotsPerRow * kMaxRows, (float*)(b + o_tf), (float*)(b + o_t), (float*)(b + o_h),
                   (bf16_t*)(b + o_v), (bf16_t*)(b + o_hb), (bf16_t*)(b + o_m), (int*)(b + o_sf), (float*)(b + o_ss), (float*)(b + o_wp),
                   (int*)(b + o_tp), (int*)(b + o_dr), (float*)(b + o_dt), tiles_even, slabs_max, off};
 }
@@ -2132,7 +2206,7 @@ void fill_common(Params& p, const DecodeWs& ws, int M, int Breq, int Kmax, const
   p.n_stages = 0; p.M = M; p.Breq = Breq; p.ad = ad; p.tenant_id = tenant_id; p.route = route; p.row_to_req = row_to_req;
   p.lora = 1;
   p.tpart = ws.tpart; p.tfin = ws.tfin; p.tcount = ws.tcount; p.tready = ws.tready; p.nc_max = shrink_chunks(Kmax);
-  p.flags = ws.flags; p.status = ws.status; p.spin_limit = g_wait_limit.load(std::memory_order_relaxed);
+  p.flags = ws.flags; p.status = ws.status; p.xflag = ws.xflag; p.xpart = ws.xpart; p.spin_limit = g_wait_limit.load(std::memory_order_relaxed);
   p.trace = nullptr;
   p.wpart = ws.wpart; p.wss = ws.wss; p.segflag = ws.segflag; p.wsegs = 0;
   p.tpflag = ws.tpflag; p.dready = ws.dready; p.delta = ws.delta; p.delta_odd = ws.delta_odd; p.slabs_max = ws.slabs_max;
@@ -2195,6 +2269,7 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     l.out_f32 = ws.h_f32; l.ld_f32 = d;
     l.out_pk = ws.h_pk;
     l.tpos0 = 3;
+    l.ksplit = 2;
     units[1] = d >> 4;
   }
   // level 2: m = silu(L_gate(n(h))) * L_up(n(h))
@@ -2215,12 +2290,14 @@ int layer_decode_packed(const bf16_t* x, int B, int d, int F, const milora_layer
     l.resid_f32 = ws.h_f32; l.ld_resid = d;
     l.out[0] = y; l.ld_out[0] = d;
     l.tpos0 = 3;
+    l.ksplit = 2;
     units[3] = d >> 4;
   }
   if (marks && marks->trace) p.trace = marks->trace;
   if (wide) {
     for (int L = 0; L < 4; ++L) {
       p.st[L] = lv[L];
+      p.st[L].ksplit = 1;
       p.st[L].lora_shrink = 1;
     }
     p.n_stages = 4;
