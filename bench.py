@@ -52,7 +52,8 @@ STREAM_PHASES = {  # (waves, slot) of milora_layer_decode_trace's stamps, few-ro
     "stream_first_input": (range(0, 6), 1), "stream_matrix_work_done": (range(0, 6), 2), "stream_tiles_summed": (range(0, 6), 3),
     "loader_barrier_passed": ([6], 1), "loader_first_chunk": ([6], 2), "loader_all_chunks": ([6], 3),
     "loader_outputs_stored": ([6], 5), "lora_shrink_items_done": ([7], 2), "lora_shrinks_published": ([7], 3),
-    "lora_expands_formed": ([7], 4), "lora_outputs_stored": ([7], 6), "flag_stored": ([7], 7)}
+    "lora_expands_formed": ([7], 4), "lora_partials_swapped": ([7], 8), "lora_outputs_stored": ([7], 6),
+    "flag_stored": ([7], 7)}
 WIDE_PHASES = {
     "level_entered": (range(0, 8), 0), "stream_first_input": (range(0, 6), 1), "stream_segments_stored": (range(0, 6), 2),
     "loader_barrier_passed": ([6], 1), "loader_copies_landed": ([6], 2), "lora_list_built": ([7], 2),
@@ -162,6 +163,16 @@ def row_rel_err(np, y, ref):
     return float((np.abs(y - ref).max(axis=1) / np.where(denom == 0, 1.0, denom)).max())
 
 
+def copy_calibration(torch, dev):
+    """A plain device copy of known size in the same process: what the byte counters read for it scales what they
+    read for the kernels."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def stack_bench(args, torch, mb, synth, wl, dev):
     """Multi-layer decode stacks (not the headline workload): every layer's packed weights and adapters resident
     in HBM, routes as a given table, one step = one token for all B requests through all L layers.  The oracle
@@ -220,6 +231,8 @@ def stack_bench(args, torch, mb, synth, wl, dev):
                                    qkv_out=qkv, workspace=ws)
             x = y
 
+    if args.copy_calibration:
+        copy_calibration(torch, dev)
     step()
     torch.cuda.synchronize()
     parity = None
@@ -367,11 +380,7 @@ def main():
         run = graph.replay
 
     if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)  # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration(torch, dev)
 
     for _ in range(args.warmup):
         run()
