@@ -66,6 +66,11 @@ struct PParams {
   int tilesM, tilesN;
 };
 
+// Which of the eight 16-byte pieces of its 128-byte LDS line holds k group kg of row r (0..15) of a block:
+// kg ^ swz(r).  Eight neighbouring rows get eight different pieces, and rows r and r + 8 (which lie 1 KiB apart, on
+// the same banks) differ too, so a 16-byte operand read of 16 rows at one k group touches every bank once.
+__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
@@ -124,7 +129,7 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
       const int rr = lane >> 3;
       int64_t r = row0 + (hh * 8 + (wave & 1) * 4 + (j >> 1)) * 16 + (j & 1) * 8 + rr;
       r = r < rlim ? r : rlim - 1;
-      voff[hh][j] = (uint32_t)((uint64_t)r * (uint32_t)p.d1 * 2u + (uint32_t)((lane & 7) ^ (rr & 7)) * 16u);
+      voff[hh][j] = (uint32_t)((uint64_t)r * (uint32_t)p.d1 * 2u + (uint32_t)((lane & 7) ^ swz((j & 1) * 8 + rr)) * 16u);
     }
   const uint32_t dst_in_half = (uint32_t)((is_w ? 8 : 0) + (wave & 1) * 4) * kBlockBytes;
   // half H = 2 * (k step) + hh lives in ring slot H % kHalves
@@ -156,7 +161,7 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
   int rd[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
-    rd[ks] = (rrow >> 4) * kBlockBytes + (rrow & 15) * 128 + (((2 * ks + (lane >> 5)) ^ (rrow & 7)) << 4);
+    rd[ks] = (rrow >> 4) * kBlockBytes + (rrow & 15) * 128 + (((2 * ks + (lane >> 5)) ^ swz(rrow & 15)) << 4);
   const unsigned char* wbase = lds + (kBlocksM / 2) * kBlockBytes;
   // One k step of 64 for the wave's 128 x 128 part: 64 matrix instructions, number q = 16 ks + 4 i + j.  The
   // operand reads come early: the sixteen of the first two sub-steps, then the other sixteen between the matrix
@@ -322,8 +327,8 @@ __global__ void __launch_bounds__(kThreadsP, 1) prefill_kernel(PParams p) {
           lo[e] = pack_bf16x2(tv[0] - bf16_to_f32(h0b), tv[1] - bf16_to_f32(h1b));
           wb[e] = bw[0] | (bw[1] << 16);
         }
-        const uint32_t o_hi = blk + (((uint32_t)g ^ (rb & 7)) << 4);
-        const uint32_t o_lo = blk + (((uint32_t)(g + 4) ^ (rb & 7)) << 4);
+        const uint32_t o_hi = blk + (((uint32_t)g ^ (uint32_t)swz(rb)) << 4);
+        const uint32_t o_lo = blk + (((uint32_t)(g + 4) ^ (uint32_t)swz(rb)) << 4);
         *(u32x4*)(lds + o_hi) = hi;
         *(u32x4*)(lds + o_lo) = lo;
         *(u32x4*)(lds + (kBlocksM / 2) * kBlockBytes + o_hi) = wb;
