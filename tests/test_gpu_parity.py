@@ -129,6 +129,22 @@ def test_route_workspace_needs_no_preparation_and_replays_in_a_graph(pool, B, d,
         assert torch.equal(route_g, eager), f"replay {rep}"
 
 
+@pytest.mark.parametrize("dtype,d,B,plen,pool", [("bf16", 200, 300, (1, 40), "mean"), ("f32", 2048, 70, (1, 130), "max"),
+                                                 ("bf16", 8192, 2, (700, 1500), "mean"), ("f32", 36, 1, (5000, 5000), "last")])
+def test_route_many_requests_wide_rows_and_single_long_prompts(dtype, d, B, plen, pool):
+    """Launch shapes of the one-kernel router the other tests do not reach: hundreds of requests of a few tokens on the
+    unvectorised path (seven slabs of 32 columns), fp32 rows of 16 slabs, two prompts of a thousand tokens cut into
+    token slices over 32 slabs, and one request alone."""
+    wl = small(dtype=dtype, d=d, T=5, B=B, prompt_len=plen, pool=pool, act="tanh", tenants="uniform", seed=d + B)
+    H, ss, sl = synth.prompts(wl, 0, DEV)
+    Wr = synth.router_weights(wl, 0, DEV)
+    tid = synth.tenant_ids(wl).to(DEV)
+    route, logits = mb.milora_route(H, ss.to(DEV), sl.to(DEV), tid, Wr, pool, "tanh")
+    ref = oracle.route(np_of(H), ss.numpy(), sl.numpy(), tid.cpu().numpy(), np_of(Wr), mb.POOL[pool], mb.ACT["tanh"])
+    assert_routes_match(route, ref, wl.torch_dtype)
+    np.testing.assert_allclose(to_f64(logits), ref.logits, atol=2e-5 * max(1.0, np.abs(ref.logits).max()))
+
+
 RATIONAL_COEF = [0.1, 1.0, 0.3, -0.2, 0.05, 0.01, -0.003, 0.5, -0.25, 0.1, 0.02, -0.01]
 
 
