@@ -618,6 +618,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         // lane, gathered row-major blocks at slot row * 4 + k group
         const int rd_off = sg.x_packed ? lane * 16 : ((lane & 15) * 4 + (lane >> 4)) * 16;
         int i = 0, cur = start_of(NCH), ac = 0;  // chunks begun, chunk index in this workgroup's rotation, tile
+        int bufi = 0;                            // i % NBUF, kept by counting: a division per chunk is paid in issue slots
         uint32_t wmask = 0xffffffffu;
         for (int r = 0; r < rounds; ++r) {
 #pragma unroll
@@ -632,7 +633,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
                   if (seen[i % kLoaders] <= lbase[i % kLoaders] + i / kLoaders) {
                     spin_until([&]() { return (seen[i % kLoaders] = ld_lds(&c.x_ready[i % kLoaders])) > lbase[i % kLoaders] + i / kLoaders; });
                   }
-                  const unsigned char* xbuf = xreg + (i % NBUF) * kChunkBytes;
+                  const unsigned char* xbuf = xreg + bufi * kChunkBytes;
 #pragma unroll
                   for (int mt = 0; mt < MT; ++mt)
                     xb[mt] = *reinterpret_cast<const u32x4*>(xbuf + ((w * MT + mt) << 10) + rd_off);
@@ -644,16 +645,18 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
                 // the chunk after it, if the loader is that far: its LDS reads overlap this k block's work
                 have_next = i + 1 < NCH && seen[(i + 1) % kLoaders] > lbase[(i + 1) % kLoaders] + (i + 1) / kLoaders;
                 if (have_next) {
-                  const unsigned char* xbuf = xreg + ((i + 1) % NBUF) * kChunkBytes;
+                  const unsigned char* xbuf = xreg + (bufi + 1 == NBUF ? 0 : bufi + 1) * kChunkBytes;
 #pragma unroll
                   for (int mt = 0; mt < MT; ++mt)
                     xn[mt] = *reinterpret_cast<const u32x4*>(xbuf + ((w * MT + mt) << 10) + rd_off);
                 }
               }
               wmask = cvalid ? 0xffffffffu : 0u;
+              if (!cvalid) {
 #pragma unroll
-              for (int mt = 0; mt < MT; ++mt) xb[mt] &= wmask;
-              if (norm) {
+                for (int mt = 0; mt < MT; ++mt) xb[mt] = u32x4{0u, 0u, 0u, 0u};
+              }
+              if (norm && cvalid) {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) ss[mt] += sumsq8(xb[mt]);
               }
@@ -672,6 +675,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
             if (++ac == NS) {
               ac = 0;
               ++i;
+              if (++bufi == NBUF) bufi = 0;
               if (++cur == NCH) cur = 0;
             }
             __builtin_amdgcn_sched_barrier(0);
