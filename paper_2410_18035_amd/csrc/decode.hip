@@ -599,9 +599,16 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       for (int a = 0; a < NSMAX; ++a)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[a][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      float ss[MT];  // sums of squares of the input rows over this wave's k blocks (normalisation)
+      // Sums of squares of the input rows over this wave's k blocks (normalisation).  Up to 32 rows the matrix cores
+      // form them: the product of an operand block with itself has them on its diagonal, one instruction per row
+      // tile and k block where the vector unit needs sixteen (the stream waves are bound by instruction issue).
+      constexpr bool kGramSS = MT <= 2;
+      float ss[MT];
+      f32x4 ssg[kGramSS ? MT : 1];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) ss[mt] = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < (kGramSS ? MT : 1); ++mt) ssg[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
       const int rounds = rounds_of(NS, NCH);
       // Ring rounds.  Slot s of a round holds tile s % NS of the wave's next k block; NS divides NSMAX and the
       // accumulator of slot s is s % NSMAX, so one piece of code serves every NS that divides NSMAX, and
@@ -657,8 +664,15 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
                 for (int mt = 0; mt < MT; ++mt) xb[mt] = u32x4{0u, 0u, 0u, 0u};
               }
               if (norm && cvalid) {
+                if constexpr (kGramSS) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) ss[mt] += sumsq8(xb[mt]);
+                  for (int mt = 0; mt < MT; ++mt)
+                    ssg[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xb[mt]), __builtin_bit_cast(bf16x8, xb[mt]),
+                                                                      ssg[mt], 0, 0, 0);
+                } else {
+#pragma unroll
+                  for (int mt = 0; mt < MT; ++mt) ss[mt] += sumsq8(xb[mt]);
+                }
               }
             }
             // Between stage ends only kSteady loads per wave stay in flight (the rest of the ring holds blocks that
@@ -717,12 +731,26 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
                 float* e = sl + ((a * MT + mt) * 4 + q) * 64 + lane;
                 *e = (pos == 0 ? 0.f : *e) + acc[a][mt][q];
               }
+        if constexpr (kGramSS) {
+          // a lane holds rows 4 (lane / 16) .. + 3 of column lane % 16 of the product: the diagonal element of row
+          // j = lane % 16 lies in the lane with lane / 16 == j / 4, at index j % 4
+          const int j = lane & 15;
+          if ((lane >> 4) == (j >> 2)) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          float v = ss[mt];
-          v += __shfl_xor(v, 16, 64);
-          v += __shfl_xor(v, 32, 64);
-          if (lane < 16) c.ss_part[w][mt * 16 + lane] = v;
+            for (int mt = 0; mt < MT; ++mt) {
+              const f32x4 g = ssg[mt];
+              const float lo = (j & 1) ? g[1] : g[0], hi = (j & 1) ? g[3] : g[2];
+              c.ss_part[w][mt * 16 + j] = (j & 2) ? hi : lo;
+            }
+          }
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            float v = ss[mt];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (lane < 16) c.ss_part[w][mt * 16 + lane] = v;
+          }
         }
         compiler_fence();
         wait_lds();
