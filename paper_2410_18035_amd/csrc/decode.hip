@@ -458,6 +458,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     c.red_free = 0;
     c.tail_go = 0;
     c.tail_done = 0;
+    c.s_flag = 0;
     c.epoch = (ld_agent(p.flags + wg) >> 4) + 1;
   }
   if (tid < 8) {
@@ -1044,6 +1045,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       TS(0);
       if (sg.sync_before && L > 0) {
         if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
+        st_lds(&c.s_flag, L);
       }
       TS(1);
       load_input(L, sg, KT, NS, NCH, NBUF, nseq, 0);
@@ -1071,7 +1073,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       if (sg.lora_shrink) lvl_tag = epoch * 16 + L + 1;  // a slot can serve several levels of one launch
       if (p.lora && sg.lora_shrink) {
         if (sg.sync_before && L > 0) {
-          if (!grid_wait(p.flags, G, epoch * 16 + L, lane, p.spin_limit)) give_up(p.status);
+          spin_until([&]() { return ld_lds(&c.s_flag) >= L; });
         }
         TS(1);
         // the rows with a LoRA term at one of this level's sites, in row order (the same list in every workgroup)
