@@ -143,6 +143,7 @@ struct Ctrl {
   int shr_ready;   // wide kernel: levels whose shrink list stands in s_rows
   int exp_next[kMaxStages];  // wide kernel: expand items of a level handed out so far
   int s_flag;
+  int bar_seen;    // wide kernel: last level whose grid barrier the loader wave has seen open
   float ss_part[kSW][kMaxRows];
   float inv_rows[kMaxRows];
   int l_ms[3 * kMaxRows];  // LoRA terms that land in this workgroup's tiles: row | site position << 8
@@ -1401,6 +1402,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
   if (tid == 0) {
     c.x_ready[0] = 0;
     c.shr_ready = 0;
+    c.bar_seen = 0;
     c.epoch = (ld_agent(p.flags + wg) >> 4) + 1;
   }
   if (tid < 8) {
@@ -1727,6 +1729,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
       // ===================================== input loader =====================================
       if (sg.sync_before && L > 0) {
         barrier_wait(epoch * 16 + L);
+        st_lds(&c.bar_seen, L);  // the LoRA wave waits for this word instead of polling the flags too
       }
       TS(1);
       const unsigned char* const Xb = reinterpret_cast<const unsigned char*>(sg.X);
@@ -1823,7 +1826,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
             }
           }
         }
-        if (sg.sync_before && L > 0) barrier_wait(epoch * 16 + L);
+        if (sg.sync_before && L > 0) spin_until([&]() { return ld_lds(&c.bar_seen) >= L; });
         asm volatile("" : : "v"(pf[0]), "v"(pf[1]), "v"(pf[2]), "v"(pf[3]), "v"(pf[4]), "v"(pf[5]), "v"(pf[6]), "v"(pf[7]));
         TS(1);
         if (have && !dead) {
