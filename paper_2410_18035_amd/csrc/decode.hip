@@ -1842,9 +1842,16 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
         __builtin_amdgcn_wave_barrier();
       }
     }
-    if (w >= kSW && p.lora && !dead) {  // loader and LoRA wave: the level's shrinks, then the expands
-      shrink_items(L, sg);
-      TS(6);
+    if (p.lora && !dead) {
+      // loader and LoRA wave: the level's shrinks, then the expands.  The stream waves, their segments stored, help
+      // with the expands: with many routed rows and large ranks (the sums wait for the last expand item) two waves
+      // per workgroup are few.
+      if (w >= kSW) {
+        shrink_items(L, sg);
+        TS(6);
+      } else {
+        spin_until([&]() { return ld_lds(&c.shr_ready) >= L + 1; });
+      }
       expand_items(L, sg);
       TS(3);
     }
