@@ -97,6 +97,12 @@ def test_argument_validation_happens_before_any_device_work():
     assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 0, null, None, 7, p, null, p, 1 << 20, null) == -1  # top_k 7
     assert L.milora_route(p, 10, 9000, 0, p, p, p, 1, 1, p, 3, 0, p, None, 1, p, null, p, 1 << 30, null) == -2  # d too large
     assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 0, null, None, 1, p, null, null, 0, null) == -5  # no workspace
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 1, 0, null, None, 1, p, null, null, 0, null) == -5  # last-token pooling needs one too
+    assert L.milora_route(p, 10, 8, 0, p, p, p, 1, 1, p, 0, 0, null, None, 1, p, null, p, 16, null) == -5  # too small
+    out = ctypes.c_double(0.0)
+    assert L.milora_measure_matrix_rate(4, 10, p, 1 << 30, ctypes.byref(out), null) == -1  # no such instruction shape
+    assert L.milora_measure_matrix_rate(1, 0, p, 1 << 30, ctypes.byref(out), null) == -1  # no iterations
+    assert L.milora_measure_matrix_rate(1, 10, null, 0, ctypes.byref(out), null) == -5  # no workspace
     ad = mb._Adapters(1, 8, 0x1000, 0x1000, 0x1000)
     assert L.milora_routed_linear(p, 1, 8, 8, 0, null, p, 0, null, ctypes.byref(ad), 9, p, p, 1, p, p, 1 << 20,
                                   null) == -1  # site 9
