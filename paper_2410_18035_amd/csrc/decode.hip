@@ -180,12 +180,15 @@ __device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // 16-byte stores of data another workgroup reads inside this launch: written through to the memory all XCDs
-// share (a plain store may stay in the writer's L2 until the launch ends).
+// share (a plain store may stay in the writer's L2 until the launch ends).  The two idle cycles behind the store
+// belong to it: a store of more than eight bytes still reads its data registers for two cycles after it issues,
+// the compiler keeps vector writes away from them only for stores it can see, and it reuses these registers at
+// once (seen: the next store's address computed into them, and address bits arriving as partial sums).
 __device__ __forceinline__ void st_through(u32x4* p, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void st_through(f32x4* p, f32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 // One 16-byte load that bypasses the caches (data stored through by another workgroup in this launch), complete
 // when the function returns.
@@ -1323,10 +1326,10 @@ __device__ __forceinline__ void shrink_finish(const Params& p, const Stage& sg, 
 }
 
 template <int MT> struct WCfg;
-// (Two k steps of weight loads in flight per wave: deeper rings only lengthen every other round trip of the launch -
-// flags, partial tiles, LoRA items - which queue behind them in the memory system.  D = 2 with CKB = 2 at 64 rows gave
-// wrong sums in the tests and is not used; the cause was not found.)
-template <> struct WCfg<4> { static constexpr int TPW = 4, D = 2, CKB = 1; };
+// (Two k steps of weight loads in flight per wave: deeper rings - three, four, six, eight steps were timed - only
+// lengthen every other round trip of the launch - flags, partial tiles, LoRA items - which queue behind them in the
+// memory system.  Chunks of two k blocks halve the stream waves' look-ups of the loader's word.)
+template <> struct WCfg<4> { static constexpr int TPW = 4, D = 2, CKB = 2; };
 template <> struct WCfg<8> { static constexpr int TPW = 2, D = 2, CKB = 2; };
 constexpr int kWideGridMax = 256;   // workgroups the segment tables are sized for
 
@@ -1372,6 +1375,23 @@ __device__ __forceinline__ void ld_through10(const f32x4* const (&q)[10], f32x4 
 }
 
 // units (tiles, or gate/up tile pairs) and groups of a level
+// Weight ring of the wide kernel: a load the compiler does not count, and the wait that makes a ring row usable
+// (at most N loads still out; the row's registers pass through the statement so that nothing that reads them moves
+// above it).
+__device__ __forceinline__ void ring_load(u32x4& dst, const gu32x4* src) {
+  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(src) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void ring_wait_n(u32x4& a, u32x4& b) {
+  static_assert(N >= 0 && N < 64, "memory counter");
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void ring_wait_n(u32x4& a, u32x4& b, u32x4& c2, u32x4& d) {
+  static_assert(N >= 0 && N < 64, "memory counter");
+  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c2), "+v"(d) : "n"(N) : "memory");
+}
+
 __device__ __host__ __forceinline__ int wide_units(const Stage& s) {
   if (s.pair) return s.N[0] >> 4;
   int t = 0;
@@ -1437,11 +1457,14 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
   // (No wave ends early here: an s_endpgm inside the item loops below made the compiler re-run an item for ever.)
   // cond() is the same in every lane (an __all, or a word every lane reads): the loop is kept scalar.
   bool dead = false;
+  // (The status word is stored from assembly: a store the compiler sees inside the weight loop makes it wait for
+  // every outstanding load at each use of the weight ring - loads and stores share the memory counter and may
+  // complete out of order, so with a store possibly pending it waits for the count to reach zero.)
   auto spin_until = [&](auto cond) __attribute__((always_inline)) {
     int spins = 0;
     while (!dead && !__builtin_amdgcn_readfirstlane((int)cond())) {
       if (++spins >= p.spin_limit) {
-        if (lane == 0) st_agent(p.status, 1);
+        if (lane == 0) asm volatile("global_store_dword %0, %1, off sc1" : : "v"(p.status), "v"(1) : "memory");
         dead = true;
       }
       __builtin_amdgcn_s_sleep(1);
@@ -1647,6 +1670,15 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           wp[j] = (const gu32x4*)sg.W[seg] + ((size_t)tile * KT + kb0) * 64 + lane;
         }
         u32x4 ring[D][TPW];
+        auto ring_wait = [&](u32x4 (&row)[TPW]) __attribute__((always_inline)) {
+          if constexpr (TPW == 2) ring_wait_n<(D - 1) * TPW>(row[0], row[1]);
+          else ring_wait_n<(D - 1) * TPW>(row[0], row[1], row[2], row[3]);
+        };
+        auto ring_drain = [&](u32x4 (&row)[TPW]) __attribute__((always_inline)) {
+          if constexpr (TPW == 2) ring_wait_n<0>(row[0], row[1]);
+          else ring_wait_n<0>(row[0], row[1], row[2], row[3]);
+        };
+        static_assert(TPW == 2 || TPW == 4, "ring_wait is written for two or four tiles per wave");
         f32x4 acc[TPW][MT];
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
@@ -1658,7 +1690,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
 #pragma unroll
         for (int s = 0; s < D; ++s)
 #pragma unroll
-          for (int j = 0; j < TPW; ++j) ring[s][j] = __builtin_nontemporal_load(wp[j] + (size_t)(s < len ? s : len - 1) * 64);
+          for (int j = 0; j < TPW; ++j) ring_load(ring[s][j], wp[j] + (size_t)(s < len ? s : len - 1) * 64);
         for (int i0 = 0; i0 < len; i0 += D) {
 #pragma unroll
           for (int s = 0; s < D; ++s) {
@@ -1682,6 +1714,10 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
 #pragma unroll
               for (int mt = 0; mt < MT; ++mt) ss[mt] += sumsq8(xb[mt]);
             }
+            // The weight blocks of this slot have landed once all but the (D - 1) TPW loads issued after them have.
+            // Loads and wait are written as assembly: with loads it can see the compiler drains every outstanding
+            // load once per pass of the ring, which leaves the ring empty at every pass.
+            ring_wait(ring[s]);
 #pragma unroll
             for (int j = 0; j < TPW; ++j) {
               const u32x4 wv = ring[s][j] & mask;
@@ -1692,7 +1728,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
             }
             const int nx = i + D < len ? i + D : len - 1;
 #pragma unroll
-            for (int j = 0; j < TPW; ++j) ring[s][j] = __builtin_nontemporal_load(wp[j] + (size_t)nx * 64);
+            for (int j = 0; j < TPW; ++j) ring_load(ring[s][j], wp[j] + (size_t)nx * 64);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -1714,6 +1750,9 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
             if (lane < 16) st_agent(p.wss + (size_t)sid * (MT * 16) + mt * 16 + lane, v);
           }
         }
+        // the ring's last, clamped loads still write their registers: those stay reserved until they have
+#pragma unroll
+        for (int s = 0; s < D; ++s) ring_drain(ring[s]);
         wait_all_mem();
         // the last of the six waves announces the segment
         int old = 0;

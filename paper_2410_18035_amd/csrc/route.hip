@@ -110,16 +110,18 @@ __device__ __forceinline__ uint8_t select_route(const float (&logit)[MILORA_NUM_
 // finishes.  The workspace needs no preparation: a tag is unique to the call, and the finishing wave wipes the tags
 // it has used (a recorded launch that is replayed meets wiped tags again).
 // Data another workgroup reads inside the launch is stored through to memory and loaded past the caches (an
-// L2 serves one XCD only); a store is acknowledged before anything that tells of it is read.
+// L2 serves one XCD only); a store is acknowledged before anything that tells of it is read.  (A 16-byte store
+// reads its data registers for two more cycles after it issues, and the compiler guards only stores it can see:
+// the idle cycles are part of the statement.)
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void st_through(f32x4* p, f32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void st_through(u32x4* p, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void st_through(u32x2* p, u32x2 v) {
   asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
