@@ -57,9 +57,12 @@ constexpr int kTraceSlots = 16;             // time stamps per (workgroup, stage
 
 // Per row-tile-count tuning: ring depth, tiles per workgroup and stage, stream waves that share a partial-tile
 // area at a stage end, bytes of LDS for LoRA expands formed ahead of the stage end.
+// (Ring depth: what a wave has asked for when a stage ends is in the way of the stage end's own round trips - stores,
+// flags, the next stage's first input.  Twelve blocks per wave, 18 MB over the chip, against twenty-four: -3.7 us per
+// layer step of the 7B shape; six: +5 us, the stream starves between stage ends.)
 template <int MT> struct Cfg;
-template <> struct Cfg<1> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELTA = 8192; };
-template <> struct Cfg<2> { static constexpr int D = 24, NS = 6, CHAIN = 1, DELTA = 8192; };
+template <> struct Cfg<1> { static constexpr int D = 12, NS = 6, CHAIN = 1, DELTA = 8192; };
+template <> struct Cfg<2> { static constexpr int D = 12, NS = 6, CHAIN = 1, DELTA = 8192; };
 template <> struct Cfg<4> { static constexpr int D = 12, NS = 6, CHAIN = 3, DELTA = 8192; };
 template <> struct Cfg<8> { static constexpr int D = 12, NS = 2, CHAIN = 3, DELTA = 2048; };
 
