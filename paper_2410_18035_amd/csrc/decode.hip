@@ -972,8 +972,10 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
         // lanes cover 64 contiguous bytes of a row, which the memory pipeline takes in one piece, and the stream
         // waves read such a block with the matching lane order.
         constexpr int LPC = kSW * MT;  // wave loads per chunk
-        constexpr int kDepth = 63 / LPC + 1;
-        static_assert(LPC <= 63, "chunk too large for the memory counter");
+        // chunks in flight: two (with one the stream waves wait for every chunk, with three to six the copies get in
+        // the way of the weight stream: 125.8, 122.7, 124.3 .. 125.2 us per layer step of the 7B shape at 32 rows)
+        constexpr int kDepth = 2;
+        static_assert(LPC * (kDepth - 1) <= 63, "chunk too large for the memory counter");
         const unsigned char* const Xb = reinterpret_cast<const unsigned char*>(sg.X);
         const bool xpk = sg.x_packed != 0;
         size_t loff[MT];  // byte offset of this lane's 16 bytes for row tile mt inside k block 0
@@ -1412,8 +1414,8 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
   constexpr int kChunk = CKB * MT * 1024;                         // bytes of an input chunk: CKB k blocks, all rows
   constexpr int NBUF = (kLdsBytes - kCtrlBytes) / kChunk;         // chunk buffers
   constexpr int LPC = CKB * MT;                                   // wave loads per chunk
-  constexpr int kDepth = (63 / LPC + 1) < NBUF ? (63 / LPC + 1) : NBUF;  // chunks the loader keeps in flight
-  static_assert(D % CKB == 0 && LPC <= 63 && NBUF >= 4, "chunks");
+  constexpr int kDepth = 16384 / kChunk > 1 ? 16384 / kChunk : 1;  // chunks the loader keeps in flight: 16 KB (64 KB cost 2.5 us per layer step)
+  static_assert(D % CKB == 0 && LPC * kDepth <= 63 && NBUF >= 4 && kDepth < NBUF, "chunks");
   extern __shared__ __align__(16) unsigned char smem[];
   Ctrl& c = *reinterpret_cast<Ctrl*>(smem);
   unsigned char* const xreg = smem + kCtrlBytes;
