@@ -52,7 +52,7 @@ STREAM_PHASES = {  # (waves, slot) of milora_layer_decode_trace's stamps, few-ro
     "stream_first_input": (range(0, 6), 1), "stream_matrix_work_done": (range(0, 6), 2), "stream_tiles_summed": (range(0, 6), 3),
     "loader_barrier_passed": ([6], 1), "loader_first_chunk": ([6], 2), "loader_all_chunks": ([6], 3),
     "loader_outputs_stored": ([6], 5), "lora_shrink_items_done": ([7], 2), "lora_shrinks_published": ([7], 3),
-    "lora_expands_formed": ([7], 4), "lora_partials_swapped": ([7], 8), "lora_outputs_stored": ([7], 6),
+    "lora_expands_formed": ([7], 4), "loader_partials_swapped": ([6], 8), "lora_outputs_stored": ([7], 6),
     "flag_stored": ([7], 7)}
 WIDE_PHASES = {
     "level_entered": (range(0, 8), 0), "stream_first_input": (range(0, 6), 1), "stream_segments_stored": (range(0, 6), 2),

@@ -282,9 +282,9 @@ int milora_layer_decode_profile(const void *x, int B, int d, int F, int dtype,
  *   dims          HOST int32 [5]: workgroups and stages of the launch, then the three array extents above
  * Stamp slots, few-row kernel (waves 0..5 stream, 6 loader, 7 LoRA): stream 0 stage entered, 1 first input chunk
  * there, 2 matrix work done, 3 partial tiles summed; loader 0 entered, 1 grid barrier passed, 2 first chunk landed,
- * 3 all landed, 4 sums complete with LoRA terms, 5 own outputs stored; LoRA 0 entered, 1 barrier passed, 2 shrink
- * items done, 3 shrinks of own rows published, 4 expands formed, 5 stream waves' sums there, 6 own outputs stored,
- * 7 hand-over flag stored, 8 partial tiles swapped with the partner (o and down stages).  Many-row kernel: all 0
+ * 3 all landed, 8 partial tiles swapped with the partner (o and down stages), 4 sums complete with LoRA terms,
+ * 5 own outputs stored; LoRA 0 entered, 1 barrier passed, 2 shrink items done, 3 shrinks of own rows published,
+ * 4 expands formed, 5 stream waves' sums there, 6 own outputs stored, 7 hand-over flag stored.  Many-row kernel: all 0
  * level entered, 4 sums begun, 5 own sums stored; stream 1 first chunk there, 2 segments stored; loader 1 barrier
  * passed, 2 copies landed, 6 shrink items done, 3 expand items done; LoRA 1 barrier passed, 2 shrink list built,
  * 8 first shrink item begun, 9 its partial flagged, 6 shrink items done, 3 expand items done.

@@ -138,6 +138,7 @@ struct Ctrl {
   int red_free;      // stages whose sums the tail waves are done with
   int tail_go;       // stages whose sums carry the LoRA terms (the loader wave may apply the glue)
   int tail_done;     // stages whose outputs the loader wave has stored
+  int swap_done;     // stages whose halves of the sums the loader wave has exchanged with the partner workgroup
   int epoch;
   int l_cnt;
   int seg_arr[8];  // wide kernel: stream waves that have stored their part of a segment (segment number % 8)
@@ -461,6 +462,7 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
     c.x_ready[0] = 0;
     c.x_ready[1] = 0;
     c.part_cnt = 0;
+    c.swap_done = 0;
     c.sum_cnt = 0;
     c.red_free = 0;
     c.tail_go = 0;
@@ -1062,6 +1064,34 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       // ---- stage end: the LoRA wave has added the LoRA terms to the sums ---------------------------------------
       float pre[8];
       glue_prefetch(L, sg, NSo, 0, pre);
+      if (sg.ksplit == 2 && NS > 0) {
+        // This wave has nothing else to do until the sums carry their LoRA terms, the LoRA wave is still forming
+        // those: the exchange runs here, beside them.
+        spin_until([&]() { return ld_lds(&c.sum_cnt) >= (L + 1) * kSW; });
+        // `red` holds this workgroup's half of the sums of tiles 2 j and 2 j + 1.  The half of the tile the partner
+        // finishes goes to memory, stored through and acknowledged before the flag; the partner's half of this
+        // workgroup's tile comes back the same way.  Sum = first half of the reduction + second half, on both sides.
+        constexpr int kTileF4 = MT * 64;  // 16-byte pieces of a tile's sums
+        const int h = wg & 1, partner = wg ^ 1;
+        const int tag = epoch * 16 + L + 1;
+        f32x4* const mine = reinterpret_cast<f32x4*>(p.xpart) + (size_t)wg * kTileF4;
+        const f32x4* const theirs = reinterpret_cast<const f32x4*>(p.xpart) + (size_t)partner * kTileF4;
+        const f32x4* const send = reinterpret_cast<const f32x4*>(red) + (1 - h) * kTileF4;
+        for (int e = lane; e < kTileF4; e += 64) st_through(mine + e, send[e]);
+        wait_all_mem();
+        if (lane == 0) st_agent(p.xflag + wg, tag);
+        spin_until([&]() { return ld_agent(p.xflag + partner) == tag; });
+        f32x4* const keep = reinterpret_cast<f32x4*>(red) + h * kTileF4;
+        f32x4* const out = reinterpret_cast<f32x4*>(red);
+        for (int e = lane; e < kTileF4; e += 64) {
+          const f32x4 got = ld_through1(theirs + e);
+          const f32x4 own = keep[e];
+          out[e] = h == 0 ? own + got : got + own;
+        }
+        wave_sync();
+        TS(8);
+        st_lds(&c.swap_done, L + 1);
+      }
       spin_until([&]() { return ld_lds(&c.tail_go) >= L + 1; });
       TS(4);
       glue(L, sg, NSo, 0, pre);
@@ -1165,30 +1195,8 @@ __global__ void __launch_bounds__(kThreads) decode_stream_kernel(const Params p)
       // ---- stage end: all six stream waves have summed their part of the tiles ---------------------------------
       spin_until([&]() { return ld_lds(&c.sum_cnt) >= (L + 1) * kSW; });
       TS(5);
-      if (sg.ksplit == 2 && NSs > 0) {
-        // `red` holds this workgroup's half of the sums of tiles 2 j and 2 j + 1.  The half of the tile the partner
-        // finishes goes to memory, stored through and acknowledged before the flag; the partner's half of this
-        // workgroup's tile comes back the same way.  Sum = first half of the reduction + second half, on both sides.
-        constexpr int kTileF4 = MT * 64;  // 16-byte pieces of a tile's sums
-        const int h = wg & 1, partner = wg ^ 1;
-        const int tag = epoch * 16 + L + 1;
-        f32x4* const mine = reinterpret_cast<f32x4*>(p.xpart) + (size_t)wg * kTileF4;
-        const f32x4* const theirs = reinterpret_cast<const f32x4*>(p.xpart) + (size_t)partner * kTileF4;
-        const f32x4* const send = reinterpret_cast<const f32x4*>(red) + (1 - h) * kTileF4;
-        for (int e = lane; e < kTileF4; e += 64) st_through(mine + e, send[e]);
-        wait_all_mem();
-        if (lane == 0) st_agent(p.xflag + wg, tag);
-        spin_until([&]() { return ld_agent(p.xflag + partner) == tag; });
-        f32x4* const keep = reinterpret_cast<f32x4*>(red) + h * kTileF4;
-        f32x4* const out = reinterpret_cast<f32x4*>(red);
-        for (int e = lane; e < kTileF4; e += 64) {
-          const f32x4 got = ld_through1(theirs + e);
-          const f32x4 own = keep[e];
-          out[e] = h == 0 ? own + got : got + own;
-        }
-        wave_sync();
-        TS(8);
-      }
+      // (o and down: the loader wave has swapped the halves of the sums with the partner workgroup meanwhile)
+      if (sg.ksplit == 2 && NSs > 0) spin_until([&]() { return ld_lds(&c.swap_done) >= L + 1; });
       for (int m = lane; m < MT * 16; m += 64) {
         float ssq = 0.f;
 #pragma unroll
