@@ -294,6 +294,17 @@ __global__ void __launch_bounds__(kPoolThreads) pool_route_kernel(PoolRouteArgs<
       all = all && g[0] == p.tag_lo && g[1] == p.tag_hi;
     }
     if (__builtin_amdgcn_readfirstlane(__ballot(all) != ~0ull)) return;
+    // Two slices that store their flags at the same time both find every flag.  Only one may go on: the second would
+    // store the slab's share again after the request's finishing wave has wiped the shares, and a replay of a
+    // recorded launch (same tag) would take that left-over share for the new one.  The one that takes the flag of
+    // slice 0 away goes on.
+    {
+      unsigned long long old = 0ull;
+      if (lane == 0)
+        old = __hip_atomic_exchange(reinterpret_cast<unsigned long long*>(flags), 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t old_lo = __builtin_amdgcn_readfirstlane((uint32_t)old), old_hi = __builtin_amdgcn_readfirstlane((uint32_t)(old >> 32));
+      if (old_lo != p.tag_lo || old_hi != p.tag_hi) return;
+    }
     for (int i = lane; i < p.S; i += 64) st_through(flags + i, u32x2{0u, 0u});
     if (f < FT) {
       const f32x4* base = reinterpret_cast<const f32x4*>(p.partial + ((size_t)b * p.C + c) * p.S * SW) + f;
