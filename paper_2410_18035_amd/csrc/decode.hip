@@ -1341,8 +1341,11 @@ __device__ __forceinline__ void shrink_finish(const Params& p, const Stage& sg, 
 template <int MT> struct WCfg;
 // (Two k steps of weight loads in flight per wave: deeper rings - three, four, six, eight steps were timed - only
 // lengthen every other round trip of the launch - flags, partial tiles, LoRA items - which queue behind them in the
-// memory system.  Chunks of two k blocks halve the stream waves' look-ups of the loader's word.)
-template <> struct WCfg<4> { static constexpr int TPW = 4, D = 2, CKB = 2; };
+// memory system.  Chunks of two k blocks halve the stream waves' look-ups of the loader's word.
+// Two tiles per wave at 64 rows as at 128, not four: groups of 12 tiles instead of 24 cut the reduction of a level into
+// half as many pieces, so half as many partial tiles go through memory, and the input copies - twice as many k blocks
+// per workgroup, 4 KiB each - are still small beside the weights: 163 -> 145 us per layer step of the 7B shape.)
+template <> struct WCfg<4> { static constexpr int TPW = 2, D = 2, CKB = 2; };
 template <> struct WCfg<8> { static constexpr int TPW = 2, D = 2, CKB = 2; };
 constexpr int kWideGridMax = 256;   // workgroups the segment tables are sized for
 
