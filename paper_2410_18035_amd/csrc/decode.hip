@@ -1344,7 +1344,8 @@ template <int MT> struct WCfg;
 // memory system.  Chunks of two k blocks halve the stream waves' look-ups of the loader's word.
 // Two tiles per wave at 64 rows as at 128, not four: groups of 12 tiles instead of 24 cut the reduction of a level into
 // half as many pieces, so half as many partial tiles go through memory, and the input copies - twice as many k blocks
-// per workgroup, 4 KiB each - are still small beside the weights: 163 -> 145 us per layer step of the 7B shape.)
+// per workgroup, 4 KiB each - are still small beside the weights: 163 -> 145 us per layer step of the 7B shape.
+// One tile per wave: 2 us less at 64 rows with four k steps in flight, 10-15 us more at 128 rows; not used.)
 template <> struct WCfg<4> { static constexpr int TPW = 2, D = 2, CKB = 2; };
 template <> struct WCfg<8> { static constexpr int TPW = 2, D = 2, CKB = 2; };
 constexpr int kWideGridMax = 256;   // workgroups the segment tables are sized for
@@ -1396,6 +1397,11 @@ __device__ __forceinline__ void ld_through10(const f32x4* const (&q)[10], f32x4 
 // above it).
 __device__ __forceinline__ void ring_load(u32x4& dst, const gu32x4* src) {
   asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(src) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void ring_wait_n(u32x4& a) {
+  static_assert(N >= 0 && N < 64, "memory counter");
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void ring_wait_n(u32x4& a, u32x4& b) {
@@ -1669,8 +1675,8 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
         for (int j = 0; j < TPW; ++j) {
           int seg = 0, tile;
           if (sg.pair) {
-            tile = g * upg + w * (TPW / 2) + (j >> 1);
-            seg = j & 1;
+            tile = g * upg + ((w * TPW + j) >> 1);  // slot w TPW + j of the group: gate and up tiles alternate
+            seg = (w * TPW + j) & 1;
             tval[j] = tile < T;
           } else {
             int u = g * NT + w * TPW + j;
@@ -1687,14 +1693,16 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
         }
         u32x4 ring[D][TPW];
         auto ring_wait = [&](u32x4 (&row)[TPW]) __attribute__((always_inline)) {
-          if constexpr (TPW == 2) ring_wait_n<(D - 1) * TPW>(row[0], row[1]);
+          if constexpr (TPW == 1) ring_wait_n<(D - 1) * TPW>(row[0]);
+          else if constexpr (TPW == 2) ring_wait_n<(D - 1) * TPW>(row[0], row[1]);
           else ring_wait_n<(D - 1) * TPW>(row[0], row[1], row[2], row[3]);
         };
         auto ring_drain = [&](u32x4 (&row)[TPW]) __attribute__((always_inline)) {
-          if constexpr (TPW == 2) ring_wait_n<0>(row[0], row[1]);
+          if constexpr (TPW == 1) ring_wait_n<0>(row[0]);
+          else if constexpr (TPW == 2) ring_wait_n<0>(row[0], row[1]);
           else ring_wait_n<0>(row[0], row[1], row[2], row[3]);
         };
-        static_assert(TPW == 2 || TPW == 4, "ring_wait is written for two or four tiles per wave");
+        static_assert(TPW == 1 || TPW == 2 || TPW == 4, "ring_wait is written for one, two or four tiles per wave");
         f32x4 acc[TPW][MT];
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
@@ -1928,7 +1936,7 @@ __global__ void __launch_bounds__(kThreads) decode_wide_kernel(const Params p) {
           if (sg.pair) {
             g = ti / upg;
             const int pi = ti - g * upg;
-            a0 = (pi / (TPW / 2)) * TPW + 2 * (pi % (TPW / 2));
+            a0 = 2 * pi;
           } else {
             g = ti / NT;
             a0 = ti - g * NT;
