@@ -119,14 +119,14 @@ extern "C" int milora_measure_matrix_rate(int shape, int iters, void* workspace,
   MILORA_HIP(hipEventCreate(&e1));
   auto* kernel = shape == 0 ? mfma_rate_kernel : mfma32_rate_kernel;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, (float*)workspace, iters < 64 ? iters : 64, mixed);
-  hipEventRecord(e0, st);
+  (void)hipEventRecord(e0, st);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, (float*)workspace, iters, mixed);
-  hipEventRecord(e1, st);
+  (void)hipEventRecord(e1, st);
   hipError_t e = hipEventSynchronize(e1);
   float ms = 0.f;
   if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (e != hipSuccess) return hip_fail(e);
   // both kernels issue 64 instructions' worth of 16x16x32 per wave and iteration: 32 of twice the size in the second
   const double flops = (double)grid * 4.0 * (double)iters * (2.0 * kAccs) * (2.0 * 16 * 16 * 32);
@@ -142,15 +142,15 @@ int time_read(const void* buf, size_t n16, int reps, int grid, void* workspace, 
   MILORA_HIP(hipEventCreate(&e0));
   MILORA_HIP(hipEventCreate(&e1));
   hipLaunchKernelGGL(read_rate_kernel<U>, dim3(grid), dim3(256), 0, st, (const u32x4*)buf, n16, (uint32_t*)workspace);
-  hipEventRecord(e0, st);
+  (void)hipEventRecord(e0, st);
   for (int r = 0; r < reps; ++r)
     hipLaunchKernelGGL(read_rate_kernel<U>, dim3(grid), dim3(256), 0, st, (const u32x4*)buf, n16, (uint32_t*)workspace);
-  hipEventRecord(e1, st);
+  (void)hipEventRecord(e1, st);
   hipError_t e = hipEventSynchronize(e1);
   float ms = 0.f;
   if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (e != hipSuccess) return hip_fail(e);
   *gbs = (double)(n16 * 16) * reps / ((double)ms * 1e-3) / 1e9;
   return check_launch();
