@@ -42,13 +42,13 @@ def test_workspace_sizes_are_monotone_and_reject_bad_sizes():
     b = mb.layer_decode_workspace_bytes(32, 4096, 11008, 32)
     assert 0 < a < b
     # above 32 rows the workspace also holds the wide-batch kernel's tables: two halves of (256 workgroups + column
-    # groups of the widest level) segments, each 96 tiles of 1 KiB partial sums (24 tiles x 4 row tiles up to 64
-    # rows, 12 x 8 above), a flag and the rows' sums of squares; 11008 / 16 gate/up pairs in groups of 12 or 6;
-    # and the LoRA term tiles (1 KiB per tile and row tile: 2 * 688 gate/up tiles + 256 of o or down) with their flags
+    # groups of the widest level) segments, each 12 tiles x the row tiles (4 up to 64 rows, 8 above) of 1 KiB partial
+    # sums, a flag and the rows' sums of squares; 11008 / 16 gate/up pairs in groups of 6; and the LoRA term tiles
+    # (1 KiB per tile and row tile: 2 * 688 gate/up tiles + 256 of o or down) with their flags
     c = mb.layer_decode_workspace_bytes(33, 4096, 11008, 32)
-    segs = 2 * (256 + 58)
+    segs = 2 * (256 + 115)
     lora_tiles = (2 * 688 + 256) * 4 * 1024
-    assert segs * (96 * 1024 + 64 * 4 + 4) + lora_tiles <= c <= segs * (96 * 1024 + 64 * 4 + 4) + lora_tiles + (1 << 23)
+    assert segs * (48 * 1024 + 64 * 4 + 4) + lora_tiles <= c <= segs * (48 * 1024 + 64 * 4 + 4) + lora_tiles + (1 << 23)
     c = mb.layer_decode_workspace_bytes(65, 4096, 11008, 32)
     segs = 2 * (256 + 115)
     lora_tiles = (2 * 688 + 256) * 8 * 1024
